@@ -1,0 +1,177 @@
+/*
+ * fvar.h -- C ABI of the late-scale block of a next-scale-prediction (VAR)
+ * model run with FasterVAR's training-free token reduction, for AMD MI355X
+ * (gfx950).
+ *
+ * One call sequence processes one transformer block at one late scale for a
+ * batch of B samples:
+ *
+ *     fvar_score_select          x[B,M,d]            -> idx_keep[B,k], idx_drop[B,M-k]
+ *     fvar_block_forward_pruned  x, idx_keep, KV     -> y_keep[B,k,d]   (appends k K/V rows)
+ *     fvar_lowrank_fill          y_keep, idx, W_c,G_c-> y[B,M,d]
+ *
+ * and fvar_block_forward_dense is the unreduced control (x[B,M,d] -> y[B,M,d],
+ * appends M K/V rows).
+ *
+ * Conventions common to every call
+ *  - Every tensor pointer is DEVICE memory owned by the caller, row-major,
+ *    contiguous, 16-byte aligned, of element type `fvar_config.dtype`
+ *    (bf16 or fp32) unless a different type is written in the signature.
+ *    The library never allocates or frees device memory; scratch space is the
+ *    caller's workspace buffer.
+ *  - Linear weights are stored "out,in": W[out][in], y = x W^T + b.
+ *  - `stream` is a hipStream_t (passed as void*; NULL = the null stream).  All
+ *    calls only enqueue work on it and return without synchronising.  The
+ *    returned status covers argument validation and launch errors, not kernel
+ *    completion.
+ *  - On any error nothing has been launched; fvar_last_error() returns a text
+ *    for the last failing call on that context.
+ *  - A context may be used from one thread at a time.  No global state.
+ *  - Index arrays are int32, strictly ascending per sample and in range; this is
+ *    the caller's contract for fvar_block_forward_pruned / fvar_lowrank_fill
+ *    (fvar_score_select produces arrays that satisfy it).
+ */
+#ifndef FVAR_H
+#define FVAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FVAR_OK = 0,
+    FVAR_ERR_INVALID_ARG = 1,   /* null / misaligned pointer, size out of range, inconsistent geometry */
+    FVAR_ERR_UNSUPPORTED = 2,   /* valid request outside what the kernels implement */
+    FVAR_ERR_WORKSPACE = 3,     /* workspace missing or smaller than fvar_*_workspace_bytes() */
+    FVAR_ERR_HIP = 4            /* a HIP runtime call or kernel launch failed */
+} fvar_status;
+
+typedef enum { FVAR_F32 = 0, FVAR_BF16 = 1 } fvar_dtype;
+
+/* Immutable geometry of the model the block belongs to.
+ * scale_hw holds 2*num_scales ints (h_1,w_1,...,h_K,w_K): the predefined scale schedule
+ * (paper, Sec. "Preliminary": token map R_k has h_k x w_k tokens).  It is copied. */
+typedef struct {
+    int32_t hidden;        /* d */
+    int32_t heads;         /* H, heads * head_dim == hidden */
+    int32_t head_dim;      /* 64 or 128 */
+    int32_t ffn_hidden;    /* F, MLP width */
+    int32_t num_scales;    /* K (may be 0 if the schedule helpers are not used) */
+    const int32_t *scale_hw;
+    fvar_dtype dtype;      /* activations, weights, KV cache, factors */
+    float ln_eps;          /* LayerNorm epsilon; 0 selects 1e-6 */
+    float attn_scale;      /* softmax scale; 0 selects 1/sqrt(head_dim) */
+} fvar_config;
+
+/* Weights of one block phi (paper: F^o = phi(F~); phi itself is never opened there; this
+ * library implements a plain pre-LayerNorm block:
+ *   u = LN1(x); [q|k|v] = u W_qkv^T + b_qkv; o = softmax(scale q K^T) V over the whole cache;
+ *   h = x + o W_o^T + b_o;  y = h + GELU_tanh(LN2(h) W_fc1^T + b_fc1) W_fc2^T + b_fc2 ).
+ * Any LayerNorm affine pointer or bias pointer may be NULL (gamma=1, beta=0, bias=0). */
+typedef struct {
+    const void *ln1_g, *ln1_b;   /* [d] */
+    const void *w_qkv, *b_qkv;   /* [3d][d], [3d]; output features ordered q | k | v, head h = columns [h*Dh,(h+1)*Dh) */
+    const void *w_o, *b_o;       /* [d][d], [d] */
+    const void *ln2_g, *ln2_b;   /* [d] */
+    const void *w_fc1, *b_fc1;   /* [F][d], [F] */
+    const void *w_fc2, *b_fc2;   /* [d][F], [d] */
+} fvar_block_weights;
+
+/* Multi-scale KV cache of one block: k and v are [B][capacity][H][Dh]; rows [0,len) of every
+ * sample hold the keys/values of the earlier scales.  The forward calls write the new rows at
+ * [len, len+rows) and read [0, len+rows); they do not change `len` (the caller advances it). */
+typedef struct {
+    void *k, *v;
+    int32_t capacity;
+    int32_t len;
+} fvar_kv;
+
+typedef struct fvar_ctx fvar_ctx;
+typedef void *fvar_stream;
+
+/* Create / destroy a context for one geometry on the current HIP device.  Host-only work. */
+fvar_status fvar_create(const fvar_config *cfg, fvar_ctx **out);
+void fvar_destroy(fvar_ctx *ctx);
+const char *fvar_last_error(const fvar_ctx *ctx);
+const char *fvar_status_string(fvar_status s);
+
+/* k = ceil(M * keep_num / keep_den) in integer arithmetic, clamped to [1, M]; -1 on bad input.
+ * (The paper fixes the number of rows r that enter the block; a keep ratio is turned into a
+ * row count here so that no float rounding can change it.) */
+int32_t fvar_keep_count(int32_t M, int32_t keep_num, int32_t keep_den);
+/* M = h_k * w_k of scale `scale_index` (0-based) and L_prev = sum of the earlier scales' tokens;
+ * -1 if the index is out of range. */
+int32_t fvar_scale_tokens(const fvar_ctx *ctx, int32_t scale_index);
+int32_t fvar_scale_prev_len(const fvar_ctx *ctx, int32_t scale_index);
+
+/* Workspace sizes in bytes (multiples of 256).  `rows` is the number of rows per sample that
+ * pass through the block: k for the pruned call, M for the dense call. */
+size_t fvar_select_workspace_bytes(const fvar_ctx *ctx, int32_t B, int32_t M);
+size_t fvar_block_workspace_bytes(const fvar_ctx *ctx, int32_t B, int32_t rows);
+
+/* Representative-token selection (paper, Sec. "Representative Token Restoration": rows of the
+ * block INPUT are ranked by their energy ||row_i||^2, the numerator of the sampling
+ * probability P_i; the index set I holds the most important rows).  Deterministic reading:
+ *   s_i = fl32(sum_j x_ij^2)   (products and sum in fp64, rounded once)
+ *   I   = the k indices that come first under (s descending, index ascending).
+ * x:[B,M,d] or NULL when scores_in is given.  scores_in:[B,M] fp32 or NULL: if given, scoring
+ * is skipped and selection runs on these values (any finite floats; -0 == +0).
+ * scores_out:[B,M] fp32 or NULL.  idx_keep:[B,k] and idx_drop:[B,M-k] (NULL allowed) receive
+ * the kept / pruned token indices in ascending order.  1 <= k <= M <= 1<<20.
+ * ws: at least fvar_select_workspace_bytes(ctx,B,M). */
+fvar_status fvar_score_select(fvar_ctx *ctx, fvar_stream stream, const void *x, int32_t B,
+                              int32_t M, int32_t k, const float *scores_in, float *scores_out,
+                              int32_t *idx_keep, int32_t *idx_drop, void *ws, size_t ws_bytes);
+
+/* Vanilla block on every token of the scale (paper, Alg. "FasterVAR", establishment stages:
+ * F_k^o = phi(F~_{k-1})).  x:[B,M,d] -> y:[B,M,d]; writes M new K/V rows per sample at
+ * kv->len and attends over kv->len + M rows.  Requires kv->len + M <= kv->capacity.
+ * x and y must not overlap.  ws: at least fvar_block_workspace_bytes(ctx,B,M). */
+fvar_status fvar_block_forward_dense(fvar_ctx *ctx, fvar_stream stream,
+                                     const fvar_block_weights *w, const void *x, int32_t B,
+                                     int32_t M, const fvar_kv *kv, void *y, void *ws,
+                                     size_t ws_bytes);
+
+/* Block on the reduced (k,d) feature (paper, Sec. "Plug-and-Play Acceleration": the (M,d) input
+ * is replaced by k rows; Alg. "FasterVAR", fidelity stage: F_r^o = phi(.)).  The k rows are
+ * the rows idx_keep of x, in idx_keep order; only they produce queries, keys and values, so
+ * attention runs over kv->len + k rows and k rows are appended to the cache.
+ * x:[B,M,d], idx_keep:[B,k] (NULL with k == M means identity), y_keep:[B,k,d] compact.
+ * ws: at least fvar_block_workspace_bytes(ctx,B,k). */
+fvar_status fvar_block_forward_pruned(fvar_ctx *ctx, fvar_stream stream,
+                                      const fvar_block_weights *w, const void *x, int32_t B,
+                                      int32_t M, const int32_t *idx_keep, int32_t k,
+                                      const fvar_kv *kv, void *y_keep, void *ws, size_t ws_bytes);
+
+/* Restoration of the full token map (paper, Eq. "redefine": rows in I come from the block
+ * output, the others from the cached counterpart feature; here each cached row is given in the
+ * rank-r restored form W_r F_r of Sec. "Random Projection" / Eq. "lstsq"):
+ *   y[b,i,:] = y_keep[b,j,:]                  if i == idx_keep[b,j]
+ *   y[b,i,:] = sum_t w_c[b,i,t] * g_c[b,t,:]  if i is in idx_drop[b,:]
+ * y_keep:[B,k,d], w_c:[B,M,r], g_c:[B,r,d], y:[B,M,d] (must not overlap y_keep).
+ * 1 <= r <= 256, r a multiple of 8 for bf16 (of 4 for fp32).  k == M (idx_drop unused) is a
+ * plain scatter.  Accumulation in fp32.  Uses no workspace. */
+fvar_status fvar_lowrank_fill(fvar_ctx *ctx, fvar_stream stream, const void *y_keep,
+                              const int32_t *idx_keep, const int32_t *idx_drop, int32_t B,
+                              int32_t M, int32_t k, int32_t r, const void *w_c, const void *g_c,
+                              void *y);
+
+/* Per-kernel timing (hipEvent pairs around every launch while enabled).  Off by default and
+ * outside any throughput measurement.  fvar_profile_read synchronises the recorded events,
+ * writes up to `cap` entries (kernel label, launches, total milliseconds) and clears them;
+ * returns the number of distinct labels. */
+typedef struct {
+    char label[48];
+    int64_t launches;
+    double total_ms;
+} fvar_profile_entry;
+fvar_status fvar_profile_enable(fvar_ctx *ctx, int32_t on);
+int32_t fvar_profile_read(fvar_ctx *ctx, fvar_profile_entry *out, int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FVAR_H */

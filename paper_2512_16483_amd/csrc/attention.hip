@@ -1,0 +1,382 @@
+// Attention of the rows that pass through the block over the whole multi-scale KV cache
+// (every cached scale is <= the current one, so all L rows are visible to every query).
+//
+// bf16 kernel, flash style, written for 64-wide wavefronts and 32x32x16 MFMA:
+//   * the score tile is computed TRANSPOSED, S^T = K Q^T (keys are the MFMA rows, queries the
+//     columns).  In the 32x32 accumulator layout a lane then owns one query column, so the
+//     running max / sum of the online softmax are lane-local scalars (one exchange with lane^32
+//     per tile), the rescale of the output accumulator is a per-lane multiply, and the
+//     probabilities are already laid out as the B operand of the second product
+//     O^T = V^T P^T -- no trip through LDS for P.
+//   * K tiles go to LDS row-major (swizzled 16 B chunks).  V tiles are transposed on their way
+//     into LDS with a register 4x8 transpose (v_perm_b32), stored [Dh][t'] where t' orders the
+//     keys the way the accumulator layout hands out P, so the V^T operand is one ds_read_b128.
+//   * global -> register prefetch of the next K/V tile overlaps the MFMAs of the current one;
+//     LDS is double buffered, one barrier per tile.
+//
+// fp32 kernel: plain tiled FMA version for the fp32 parity configuration.
+#include "common.h"
+
+namespace fvar {
+
+constexpr int BT = 64;                       // keys per tile
+
+template <int DH, int NQ>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restrict__ q,
+                                                        const uint16_t *__restrict__ Kc,
+                                                        const uint16_t *__restrict__ Vc, int n, int L,
+                                                        int cap, int H, float c_log2,
+                                                        uint16_t *__restrict__ o)
+{
+    constexpr int KS = DH / 16;              // k16 steps of the QK product
+    constexpr int DB = DH / 32;              // 32-row blocks of O^T
+    constexpr int KCH = DH / 8;              // 16 B chunks per K row
+    constexpr int LK = BT * KCH / 256;       // K chunks per thread per tile
+    constexpr int VBLK = (BT / 4) * (DH / 8);        // 4x8 transpose blocks per V tile
+    constexpr int LV = (VBLK + 255) / 256;
+    constexpr int KTILE = BT * DH, STAGE = 2 * KTILE;
+
+    extern __shared__ uint4 lds_raw[];
+    uint16_t *lds = reinterpret_cast<uint16_t *>(lds_raw);   // [stage][K tile | V^T tile]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rl = lane & 31, g = lane >> 5;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int q0 = blockIdx.x * (128 * NQ) + wave * (32 * NQ);
+    const size_t rowpitch = (size_t)H * DH;
+    const uint16_t *Kb = Kc + ((size_t)b * cap * H + h) * DH;
+    const uint16_t *Vb = Vc + ((size_t)b * cap * H + h) * DH;
+
+    // ---- Q fragments (B operand: lane = query column, 8 consecutive head-dim values)
+    bf16x8_t qf[NQ][KS];
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        const int row = min(q0 + j * 32 + rl, n - 1);
+        const uint16_t *src = q + ((size_t)b * n + row) * rowpitch + (size_t)h * DH + 8 * g;
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            qf[j][s] = *reinterpret_cast<const bf16x8_t *>(src + 16 * s);
+    }
+
+    // ---- staging assignment
+    int k_row[LK], k_chk[LK];
+#pragma unroll
+    for (int i = 0; i < LK; ++i) {
+        const int id = tid + 256 * i;
+        k_row[i] = id / KCH;
+        k_chk[i] = id % KCH;
+    }
+    // V block: 4 key rows x 8 head-dim columns.  tb4 = 2*chunk + half; chunk = 2*w + gg covers
+    // keys 16w + 8a + 4gg + jj (a = half, jj = 0..3): the order in which a lane's accumulator
+    // entries enumerate the keys of a 16-key MFMA step.
+    int v_t0[LV], v_col[LV], v_dst[LV];
+    bool v_on[LV];
+#pragma unroll
+    for (int i = 0; i < LV; ++i) {
+        const int blk = tid + 256 * i;
+        v_on[i] = blk < VBLK;
+        const int cb = blk % (DH / 8), tb4 = (blk / (DH / 8)) % (BT / 4);
+        const int chunk = tb4 >> 1, a = tb4 & 1, w = chunk >> 1, gg = chunk & 1;
+        v_t0[i] = 16 * w + 8 * a + 4 * gg;
+        v_col[i] = cb * 8;
+        v_dst[i] = chunk * 8 + a * 4;        // element offset inside an unswizzled V^T row
+    }
+
+    uint4 kreg[LK];
+    uint4 vreg[LV][4];
+    auto load_tile = [&](int t0) {
+#pragma unroll
+        for (int i = 0; i < LK; ++i) {
+            const int t = min(t0 + k_row[i], L - 1);
+            kreg[i] = *reinterpret_cast<const uint4 *>(Kb + (size_t)t * rowpitch + k_chk[i] * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < LV; ++i) {
+            if (!v_on[i]) continue;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int t = min(t0 + v_t0[i] + jj, L - 1);
+                vreg[i][jj] = *reinterpret_cast<const uint4 *>(Vb + (size_t)t * rowpitch + v_col[i]);
+            }
+        }
+    };
+    auto store_tile = [&](uint16_t *st) {
+#pragma unroll
+        for (int i = 0; i < LK; ++i)
+            *reinterpret_cast<uint4 *>(st + k_row[i] * DH + ((k_chk[i] ^ (k_row[i] & 7)) << 3)) =
+                kreg[i];
+        uint16_t *vt = st + KTILE;
+#pragma unroll
+        for (int i = 0; i < LV; ++i) {
+            if (!v_on[i]) continue;
+            const uint32_t *w0 = reinterpret_cast<const uint32_t *>(&vreg[i][0]);
+            const uint32_t *w1 = reinterpret_cast<const uint32_t *>(&vreg[i][1]);
+            const uint32_t *w2 = reinterpret_cast<const uint32_t *>(&vreg[i][2]);
+            const uint32_t *w3 = reinterpret_cast<const uint32_t *>(&vreg[i][3]);
+            const int chunk = v_dst[i] >> 3, sub = v_dst[i] & 7;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                uint2 lo, hi;
+                lo.x = __builtin_amdgcn_perm(w1[m], w0[m], 0x05040100u);
+                lo.y = __builtin_amdgcn_perm(w3[m], w2[m], 0x05040100u);
+                hi.x = __builtin_amdgcn_perm(w1[m], w0[m], 0x07060302u);
+                hi.y = __builtin_amdgcn_perm(w3[m], w2[m], 0x07060302u);
+                const int d0 = v_col[i] + 2 * m, d1 = d0 + 1;
+                *reinterpret_cast<uint2 *>(vt + d0 * BT + ((chunk ^ (d0 & 7)) << 3) + sub) = lo;
+                *reinterpret_cast<uint2 *>(vt + d1 * BT + ((chunk ^ (d1 & 7)) << 3) + sub) = hi;
+            }
+        }
+    };
+
+    floatx16_t oacc[DB][NQ];
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) oacc[i][j] = floatx16_t{0};
+    float m_run[NQ], l_run[NQ];
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) { m_run[j] = -INFINITY; l_run[j] = 0.f; }
+
+    load_tile(0);
+    store_tile(lds);
+    __syncthreads();
+
+    const int ntiles = (L + BT - 1) / BT;
+    for (int it = 0; it < ntiles; ++it) {
+        const uint16_t *ks = lds + (it & 1) * STAGE;
+        const uint16_t *vt = ks + KTILE;
+        const bool more = it + 1 < ntiles;
+        if (more) load_tile((it + 1) * BT);
+
+        // ---- S^T = K Q^T : [64 keys] x [32*NQ queries]
+        floatx16_t sacc[2][NQ];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int j = 0; j < NQ; ++j) sacc[tb][j] = floatx16_t{0};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                const int r = tb * 32 + rl;
+                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(
+                    ks + r * DH + (((2 * s + g) ^ (r & 7)) << 3));
+#pragma unroll
+                for (int j = 0; j < NQ; ++j)
+                    sacc[tb][j] =
+                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[j][s], sacc[tb][j], 0, 0, 0);
+            }
+        }
+        // ---- mask the ragged tail of the cache
+        const int t0 = it * BT;
+        if (t0 + BT > L) {
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int t = t0 + tb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+                    if (t >= L) {
+#pragma unroll
+                        for (int j = 0; j < NQ; ++j) sacc[tb][j][i] = -INFINITY;
+                    }
+                }
+        }
+        // ---- online softmax, one query column per lane
+        bf16x8_t pf[4][NQ];
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+            float mx = sacc[0][j][0];
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[tb][j][i]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[j], mx);
+            const float alpha = exp2f((m_run[j] - m_new) * c_log2);
+            const float mc = m_new * c_log2;
+            m_run[j] = m_new;
+            float psum = 0.f;
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                float p[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    p[i] = exp2f(fmaf(sacc[tb][j][i], c_log2, -mc));
+                    psum += p[i];
+                }
+#pragma unroll
+                for (int uu = 0; uu < 2; ++uu) {
+                    uint4 pk;
+                    pk.x = pack_bf16x2(p[8 * uu + 0], p[8 * uu + 1]);
+                    pk.y = pack_bf16x2(p[8 * uu + 2], p[8 * uu + 3]);
+                    pk.z = pack_bf16x2(p[8 * uu + 4], p[8 * uu + 5]);
+                    pk.w = pack_bf16x2(p[8 * uu + 6], p[8 * uu + 7]);
+                    pf[2 * tb + uu][j] = __builtin_bit_cast(bf16x8_t, pk);
+                }
+            }
+            l_run[j] = l_run[j] * alpha + psum;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[db][j][i] *= alpha;
+        }
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const int dr = db * 32 + rl;
+                const bf16x8_t vf = *reinterpret_cast<const bf16x8_t *>(
+                    vt + dr * BT + (((2 * u + g) ^ (dr & 7)) << 3));
+#pragma unroll
+                for (int j = 0; j < NQ; ++j)
+                    oacc[db][j] =
+                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u][j], oacc[db][j], 0, 0, 0);
+            }
+        }
+        if (more) store_tile(lds + ((it + 1) & 1) * STAGE);
+        __syncthreads();
+    }
+
+    // ---- normalise and store: lane = query, 4 consecutive head-dim values per accumulator group
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        const int row = q0 + j * 32 + rl;
+        const float l = l_run[j] + __shfl_xor(l_run[j], 32);
+        const float inv = 1.0f / l;
+        if (row >= n) continue;
+        uint16_t *dst = o + ((size_t)b * n + row) * rowpitch + (size_t)h * DH;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; e += 4) {
+                const int dh = db * 32 + 8 * (e >> 2) + 4 * g;
+                uint2 pk;
+                pk.x = pack_bf16x2(oacc[db][j][e] * inv, oacc[db][j][e + 1] * inv);
+                pk.y = pack_bf16x2(oacc[db][j][e + 2] * inv, oacc[db][j][e + 3] * inv);
+                *reinterpret_cast<uint2 *>(dst + dh) = pk;
+            }
+    }
+}
+
+template <int DH, int NQ>
+static void launch_attn_bf16(const void *q, const void *K, const void *V, int B, int n, int L,
+                             int cap, int H, float scale, void *o, hipStream_t st)
+{
+    constexpr int BQ = 128 * NQ;
+    const size_t lds = (size_t)2 * 2 * BT * DH * sizeof(uint16_t);
+    auto kern = attn_bf16_kernel<DH, NQ>;
+    static bool attr_set = false;
+    if (!attr_set && lds > 48 * 1024) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_set = true;
+    }
+    dim3 grid((n + BQ - 1) / BQ, H, B), block(256);
+    hipLaunchKernelGGL(kern, grid, block, lds, st, (const uint16_t *)q, (const uint16_t *)K,
+                       (const uint16_t *)V, n, L, cap, H, scale * 1.4426950408889634f,
+                       (uint16_t *)o);
+}
+
+// ------------------------------------------------------------------------------ fp32
+template <int DH>
+__global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__ q,
+                                                       const float *__restrict__ Kc,
+                                                       const float *__restrict__ Vc, int n, int L,
+                                                       int cap, int H, float scale,
+                                                       float *__restrict__ o)
+{
+    constexpr int TQ = 32, TK = 32, OC = DH / 8;
+    __shared__ float Qs[TQ][DH + 1];
+    __shared__ float Ks[TK][DH + 1];
+    __shared__ float Vs[TK][DH];
+    __shared__ float Ps[TQ][TK + 1];
+    const int tid = threadIdx.x, ty = tid >> 3, tx = tid & 7;     // row ty, 4 key columns at tx*4
+    const int h = blockIdx.y, b = blockIdx.z, q0 = blockIdx.x * TQ;
+    const size_t rowpitch = (size_t)H * DH;
+    for (int e = tid; e < TQ * DH; e += 256) {
+        const int r = e / DH, c = e % DH;
+        Qs[r][c] = q[((size_t)b * n + min(q0 + r, n - 1)) * rowpitch + (size_t)h * DH + c];
+    }
+    float acc[OC];
+#pragma unroll
+    for (int c = 0; c < OC; ++c) acc[c] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    for (int t0 = 0; t0 < L; t0 += TK) {
+        __syncthreads();
+        for (int e = tid; e < TK * DH; e += 256) {
+            const int r = e / DH, c = e % DH;
+            const size_t off = ((size_t)b * cap + min(t0 + r, L - 1)) * rowpitch + (size_t)h * DH + c;
+            Ks[r][c] = Kc[off];
+            Vs[r][c] = Vc[off];
+        }
+        __syncthreads();
+        float s[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float d = 0.f;
+            for (int e = 0; e < DH; ++e) d = fmaf(Qs[ty][e], Ks[tx * 4 + c][e], d);
+            s[c] = (t0 + tx * 4 + c < L) ? d * scale : -INFINITY;
+        }
+        float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+        mx = fmaxf(mx, __shfl_xor(mx, 1));
+        mx = fmaxf(mx, __shfl_xor(mx, 2));
+        mx = fmaxf(mx, __shfl_xor(mx, 4));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = expf(m_run - m_new);
+        float ps = 0.f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float p = expf(s[c] - m_new);
+            Ps[ty][tx * 4 + c] = p;
+            ps += p;
+        }
+        ps += __shfl_xor(ps, 1);
+        ps += __shfl_xor(ps, 2);
+        ps += __shfl_xor(ps, 4);
+        l_run = l_run * alpha + ps;
+        m_run = m_new;
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < OC; ++c) acc[c] *= alpha;
+        for (int t = 0; t < TK; ++t) {
+            const float p = Ps[ty][t];
+#pragma unroll
+            for (int c = 0; c < OC; ++c) acc[c] = fmaf(p, Vs[t][tx * OC + c], acc[c]);
+        }
+    }
+    const int row = q0 + ty;
+    if (row < n) {
+        float *dst = o + ((size_t)b * n + row) * rowpitch + (size_t)h * DH + tx * OC;
+        const float inv = 1.0f / l_run;
+#pragma unroll
+        for (int c = 0; c < OC; ++c) dst[c] = acc[c] * inv;
+    }
+}
+
+void launch_attention(DType dt, const void *q, const void *K, const void *V, int B, int n, int L,
+                      int cap, int H, int Dh, float scale, void *o, hipStream_t st)
+{
+    if (dt == DType::BF16) {
+        // two 32-query blocks per wavefront halve the LDS operand traffic per MFMA; use the
+        // single-block variant when that would leave most of a 256-query tile empty
+        const bool wide = (n % 256 == 0) || (n % 256 > 128);
+        if (Dh == 64) {
+            if (wide) launch_attn_bf16<64, 2>(q, K, V, B, n, L, cap, H, scale, o, st);
+            else launch_attn_bf16<64, 1>(q, K, V, B, n, L, cap, H, scale, o, st);
+        } else {
+            if (wide) launch_attn_bf16<128, 2>(q, K, V, B, n, L, cap, H, scale, o, st);
+            else launch_attn_bf16<128, 1>(q, K, V, B, n, L, cap, H, scale, o, st);
+        }
+    } else {
+        dim3 grid((n + 31) / 32, H, B), block(256);
+        if (Dh == 64)
+            hipLaunchKernelGGL(attn_f32_kernel<64>, grid, block, 0, st, (const float *)q,
+                               (const float *)K, (const float *)V, n, L, cap, H, scale, (float *)o);
+        else
+            hipLaunchKernelGGL(attn_f32_kernel<128>, grid, block, 0, st, (const float *)q,
+                               (const float *)K, (const float *)V, n, L, cap, H, scale, (float *)o);
+    }
+}
+
+}  // namespace fvar

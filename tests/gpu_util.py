@@ -1,0 +1,119 @@
+"""Helpers of the GPU parity tests: run the HIP path through the C ABI on numpy inputs and run
+the CPU oracle on the same inputs."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2512_16483_amd as fv
+
+TOL = {"bf16": 2e-2, "f32": 1e-4}
+
+
+def tdtype(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def to_dev(a, dtype: str):
+    if a is None:
+        return None
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to("cuda").to(tdtype(dtype)).contiguous()
+
+
+def to_np(t) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max_i |g_i - o_i| / max(|o_i|, rms(o)): element-wise relative error with an rms floor."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = np.sqrt(np.mean(ref ** 2))
+    den = np.maximum(np.abs(ref), max(rms, 1e-30))
+    return float(np.max(np.abs(got - ref) / den))
+
+
+class GpuBlock:
+    """One block's device state: context, weights, KV cache with the prefix loaded, workspace."""
+
+    def __init__(self, d, H, F, dtype, weights: dict, Kp: np.ndarray, Vp: np.ndarray, cap: int,
+                 scales=()):
+        self.d, self.H, self.Dh, self.F, self.dtype = d, H, d // H, F, dtype
+        self.ctx = fv.Context(hidden=d, heads=H, head_dim=d // H, ffn_hidden=F, scales=scales,
+                              dtype=dtype)
+        self.w = {k: to_dev(v, dtype) for k, v in weights.items()}
+        B, Lp = Kp.shape[0], Kp.shape[1]
+        self.B, self.Lp, self.cap = B, Lp, cap
+        self.K = torch.zeros((B, cap, H, self.Dh), dtype=tdtype(dtype), device="cuda")
+        self.V = torch.zeros_like(self.K)
+        self.K[:, :Lp] = to_dev(Kp, dtype)
+        self.V[:, :Lp] = to_dev(Vp, dtype)
+
+    def _ws(self, rows):
+        n = fv.fvar_block_workspace_bytes(self.ctx, self.B, rows)
+        return torch.empty(n, dtype=torch.uint8, device="cuda")
+
+    def score_select(self, x, k, scores_in=None):
+        B, M, _ = x.shape
+        idx_keep = torch.full((B, k), -1, dtype=torch.int32, device="cuda")
+        idx_drop = torch.full((B, M - k), -1, dtype=torch.int32, device="cuda")
+        scores = torch.empty((B, M), dtype=torch.float32, device="cuda")
+        fv.fvar_score_select(self.ctx, x, B, M, k, idx_keep, idx_drop, scores_in=scores_in,
+                             scores_out=scores)
+        return scores, idx_keep, idx_drop
+
+    def pruned(self, x, idx_keep, k):
+        B, M, d = x.shape
+        y_keep = torch.empty((B, k, d), dtype=x.dtype, device="cuda")
+        fv.fvar_block_forward_pruned(self.ctx, self.w, x, B, M, idx_keep, k, self.K, self.V,
+                                     self.cap, self.Lp, y_keep, self._ws(k))
+        return y_keep
+
+    def dense(self, x):
+        B, M, d = x.shape
+        y = torch.empty_like(x)
+        fv.fvar_block_forward_dense(self.ctx, self.w, x, B, M, self.K, self.V, self.cap, self.Lp, y,
+                                    self._ws(M))
+        return y
+
+    def fill(self, y_keep, idx_keep, idx_drop, M, Wc, Gc):
+        B, k, d = y_keep.shape
+        y = torch.full((B, M, d), float("nan"), dtype=y_keep.dtype, device="cuda")
+        r = Gc.shape[1] if Gc is not None else 0
+        fv.fvar_lowrank_fill(self.ctx, y_keep, idx_keep, idx_drop, B, M, k, r, Wc, Gc, y)
+        return y
+
+
+def oracle_pruned(x, k, weights, H, Kp, Vp, Wc, Gc):
+    """Oracle over the batch; returns dict of stacked outputs and the appended K/V rows."""
+    B, M, d = x.shape
+    Lp = Kp.shape[1]
+    w = oracle.BlockWeights(**weights)
+    outs = []
+    Kn, Vn = [], []
+    for b in range(B):
+        Kc = np.zeros((Lp + k, H, d // H), np.float32)
+        Vc = np.zeros_like(Kc)
+        Kc[:Lp], Vc[:Lp] = Kp[b], Vp[b]
+        outs.append(oracle.pruned_step(x[b], k, w, H, Kc, Vc, Lp, Wc[b], Gc[b]))
+        Kn.append(Kc[Lp:]); Vn.append(Vc[Lp:])
+    res = {key: np.stack([o[key] for o in outs]) for key in outs[0]}
+    res["K_new"], res["V_new"] = np.stack(Kn), np.stack(Vn)
+    return res
+
+
+def oracle_dense(x, weights, H, Kp, Vp):
+    B, M, d = x.shape
+    Lp = Kp.shape[1]
+    w = oracle.BlockWeights(**weights)
+    ys, Kn, Vn = [], [], []
+    for b in range(B):
+        Kc = np.zeros((Lp + M, H, d // H), np.float32)
+        Vc = np.zeros_like(Kc)
+        Kc[:Lp], Vc[:Lp] = Kp[b], Vp[b]
+        ys.append(oracle.block_forward(x[b], w, H, Kc, Vc, Lp))
+        Kn.append(Kc[Lp:]); Vn.append(Vc[Lp:])
+    return np.stack(ys), np.stack(Kn), np.stack(Vn)

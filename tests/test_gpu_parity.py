@@ -1,0 +1,239 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle on the same seeded inputs.
+
+Bars: indices bit-exact; bf16 outputs within 2e-2, fp32 outputs within 1e-4, both measured as
+max_i |g_i - o_i| / max(|o_i|, rms(o))."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import factors
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import (TOL, GpuBlock, oracle_dense, oracle_pruned, rel_err, tdtype, to_dev,  # noqa: E402
+                      to_np)
+
+
+def make_case(dtype, B, M, d, H, F, Lp, r, seed, std=0.02, bias=False, affine=False, noise=0.05,
+              iid=False):
+    bf = dtype == "bf16"
+    x = (wl.activations_iid if iid else wl.activations_lowrank)(B, M, d, seed=seed, bf16=bf)
+    w = wl.block_weights(d, F, seed=seed + 1, bf16=bf, std=std, with_bias=bias, with_affine=affine)
+    Kp, Vp = wl.kv_prefix(B, Lp, H, d // H, seed=seed + 2, bf16=bf)
+    Cm = wl.cached_feature(B, M, d, r, seed=seed + 3, noise=noise)
+    z = wl.normal_draws(B, M, r, seed=seed + 4)
+    Wc = np.empty((B, M, r), np.float32)
+    Gc = np.empty((B, r, d), np.float32)
+    for b in range(B):
+        Wc[b], Gc[b] = factors.cache_factors(Cm[b], z[b])
+    if bf:
+        Wc, Gc = wl.round_to_bf16(Wc), wl.round_to_bf16(Gc)
+    return x, w, Kp, Vp, Wc, Gc
+
+
+# ----------------------------------------------------------------------------- score + select
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,M,d", [(1, 1, 64), (2, 63, 128), (3, 257, 1920), (2, 1024, 2048),
+                                   (1, 1600, 4096)])
+def test_scores_and_indices_bitexact(dtype, B, M, d):
+    x = wl.activations_lowrank(B, M, d, seed=17 + M, bf16=dtype == "bf16")
+    blk = GpuBlock(d, d // 64, 64 * 4, dtype, {}, np.zeros((B, 0, d // 64, 64), np.float32),
+                   np.zeros((B, 0, d // 64, 64), np.float32), 1)
+    xd = to_dev(x, dtype)
+    for k in sorted({1, max(1, M // 3), M}):
+        s, keep, drop = blk.score_select(xd, k)
+        torch.cuda.synchronize()
+        for b in range(B):
+            so = oracle.scores(x[b])
+            assert np.array_equal(to_np(s[b]), so), "scores differ from the oracle's fp32 scores"
+            ko, do = oracle.topk(so, k)
+            assert np.array_equal(keep[b].cpu().numpy(), ko)
+            assert np.array_equal(drop[b].cpu().numpy(), do)
+
+
+@pytest.mark.parametrize("M", [1, 2, 64, 65, 1000, 1024, 1025, 6400, 12288, 13001])
+def test_select_on_given_scores(M):
+    rng = np.random.default_rng(M)
+    blk = GpuBlock(64, 1, 64, "f32", {}, np.zeros((1, 0, 1, 64), np.float32),
+                   np.zeros((1, 0, 1, 64), np.float32), 1)
+    cases = [rng.standard_normal(M).astype(np.float32) ** 2,
+             np.full(M, 3.25, np.float32),                                  # all equal
+             np.round(rng.standard_normal(M) * 2).astype(np.float32),       # heavy ties, negatives, +-0
+             np.arange(M, dtype=np.float32),                                # ascending
+             -np.arange(M, dtype=np.float32),                               # descending
+             (rng.integers(0, 3, M) * 1e-30).astype(np.float32)]            # tiny values, many ties
+    cases[2][::7] = -0.0
+    S = np.stack(cases)
+    B = S.shape[0]
+    sd = torch.from_numpy(S).cuda()
+    for k in sorted({1, 2, M // 2, M - 1, M} - {0}):
+        if k > M:
+            continue
+        _, keep, drop = blk.score_select(torch.empty((B, M, 64), device="cuda"), k, scores_in=sd)
+        torch.cuda.synchronize()
+        for b in range(B):
+            ko, do = oracle.topk(S[b], k)
+            assert np.array_equal(keep[b].cpu().numpy(), ko), (M, k, b)
+            assert np.array_equal(drop[b].cpu().numpy(), do), (M, k, b)
+
+
+# ----------------------------------------------------------------------------- fill
+@pytest.mark.parametrize("dtype,r", [("bf16", 8), ("bf16", 64), ("bf16", 72), ("bf16", 128),
+                                     ("bf16", 256), ("f32", 4), ("f32", 32), ("f32", 100)])
+@pytest.mark.parametrize("M,d,k", [(300, 1920, 120), (64, 128, 1), (129, 256, 129), (130, 192, 0)])
+def test_lowrank_fill(dtype, r, M, d, k):
+    bf = dtype == "bf16"
+    B = 2
+    rng = np.random.default_rng(r + M)
+    Wc = rng.standard_normal((B, M, r)).astype(np.float32)
+    Gc = (rng.standard_normal((B, r, d)) / np.sqrt(r)).astype(np.float32)
+    yk = rng.standard_normal((B, k, d)).astype(np.float32)
+    if bf:
+        Wc, Gc, yk = wl.round_to_bf16(Wc), wl.round_to_bf16(Gc), wl.round_to_bf16(yk)
+    keep = np.stack([np.sort(rng.permutation(M)[:k]) for _ in range(B)]).astype(np.int32).reshape(B, k)
+    drop = np.stack([np.setdiff1d(np.arange(M), keep[b]) for b in range(B)]).astype(np.int32)
+    blk = GpuBlock(d, d // 64, 256, dtype, {}, np.zeros((B, 0, d // 64, 64), np.float32),
+                   np.zeros((B, 0, d // 64, 64), np.float32), 1)
+    y = blk.fill(to_dev(yk, dtype), torch.from_numpy(keep).cuda(), torch.from_numpy(drop).cuda(), M,
+                 to_dev(Wc, dtype), to_dev(Gc, dtype))
+    torch.cuda.synchronize()
+    y = to_np(y)
+    assert np.isfinite(y).all(), "some row was never written"
+    for b in range(B):
+        ref = oracle.lowrank_fill(yk[b], keep[b], drop[b], M, Wc[b], Gc[b])
+        assert np.array_equal(y[b][keep[b]], yk[b])                       # kept rows are copies
+        assert rel_err(y[b], ref) <= TOL[dtype]
+
+
+# ----------------------------------------------------------------------------- block, small shapes
+SMALL = [  # dtype, B, M, d, H, F, Lp, k, r
+    ("bf16", 2, 96, 128, 2, 256, 37, 40, 16),
+    ("bf16", 1, 300, 256, 2, 512, 129, 131, 32),     # head_dim 128, ragged tiles
+    ("bf16", 3, 70, 256, 4, 320, 1, 1, 8),           # one kept row, one cached key
+    ("bf16", 1, 200, 384, 6, 768, 500, 200, 24),     # keep everything
+    ("f32", 2, 96, 128, 2, 256, 37, 40, 16),
+    ("f32", 1, 150, 256, 2, 512, 65, 33, 8),         # head_dim 128
+]
+
+
+@pytest.mark.parametrize("dtype,B,M,d,H,F,Lp,k,r", SMALL)
+@pytest.mark.parametrize("extras", [False, True])
+def test_pruned_path_small(dtype, B, M, d, H, F, Lp, k, r, extras):
+    x, w, Kp, Vp, Wc, Gc = make_case(dtype, B, M, d, H, F, Lp, r, seed=100 + M, std=0.08,
+                                     bias=extras, affine=extras)
+    ref = oracle_pruned(x, k, w, H, Kp, Vp, Wc, Gc)
+    blk = GpuBlock(d, H, F, dtype, w, Kp, Vp, Lp + M)
+    xd = to_dev(x, dtype)
+    s, keep, drop = blk.score_select(xd, k)
+    y_keep = blk.pruned(xd, keep, k)
+    y = blk.fill(y_keep, keep, drop, M, to_dev(Wc, dtype), to_dev(Gc, dtype))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(s), ref["scores"])
+    assert np.array_equal(keep.cpu().numpy(), ref["idx_keep"])
+    assert np.array_equal(drop.cpu().numpy(), ref["idx_drop"])
+    tol = TOL[dtype]
+    assert rel_err(to_np(blk.K[:, Lp:Lp + k]), ref["K_new"]) <= tol
+    assert rel_err(to_np(blk.V[:, Lp:Lp + k]), ref["V_new"]) <= tol
+    assert rel_err(to_np(y_keep), ref["y_keep"]) <= tol
+    assert rel_err(to_np(y), ref["y"]) <= tol
+    assert np.array_equal(to_np(blk.K[:, :Lp]), Kp)                        # prefix untouched
+
+
+@pytest.mark.parametrize("dtype,B,M,d,H,F,Lp,k,r", SMALL[:2] + SMALL[4:5])
+def test_dense_block_small_and_keep_all(dtype, B, M, d, H, F, Lp, k, r):
+    x, w, Kp, Vp, Wc, Gc = make_case(dtype, B, M, d, H, F, Lp, r, seed=300 + M, std=0.08, bias=True)
+    yo, Kn, Vn = oracle_dense(x, w, H, Kp, Vp)
+    blk = GpuBlock(d, H, F, dtype, w, Kp, Vp, Lp + M)
+    xd = to_dev(x, dtype)
+    y = blk.dense(xd)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert rel_err(to_np(y), yo) <= tol
+    assert rel_err(to_np(blk.K[:, Lp:]), Kn) <= tol and rel_err(to_np(blk.V[:, Lp:]), Vn) <= tol
+    # keep ratio 1.0: the pruned entry point with every row kept gives the dense result bit for bit
+    blk2 = GpuBlock(d, H, F, dtype, w, Kp, Vp, Lp + M)
+    _, keep, drop = blk2.score_select(xd, M)
+    assert np.array_equal(keep.cpu().numpy(), np.tile(np.arange(M, dtype=np.int32), (B, 1)))
+    y2 = blk2.pruned(xd, keep, M)
+    y3 = blk2.fill(y2, keep, drop, M, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y) and torch.equal(y3, y)
+    assert torch.equal(blk2.K, blk.K) and torch.equal(blk2.V, blk.V)
+
+
+def test_runs_are_deterministic():
+    dtype, B, M, d, H, F, Lp, k, r = SMALL[1]
+    x, w, Kp, Vp, Wc, Gc = make_case(dtype, B, M, d, H, F, Lp, r, seed=7)
+    outs = []
+    for _ in range(2):
+        blk = GpuBlock(d, H, F, dtype, w, Kp, Vp, Lp + M)
+        xd = to_dev(x, dtype)
+        _, keep, drop = blk.score_select(xd, k)
+        y = blk.fill(blk.pruned(xd, keep, k), keep, drop, M, to_dev(Wc, dtype), to_dev(Gc, dtype))
+        torch.cuda.synchronize()
+        outs.append((y.clone(), blk.K.clone()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
+# ----------------------------------------------------------------------------- real shapes
+def test_var_d16_last_scale_fp32_full():
+    """The fp32 configuration at its full size: 256 tokens, 424 cached rows, keep 0.5, r = 32."""
+    W = wl.WORKLOADS["var_d16_s16_f32"]
+    side = 16
+    M, Lp, k = W.tokens(side), W.prev_len(side), W.keep(side)
+    x, w, Kp, Vp, Wc, Gc = make_case("f32", 1, M, W.hidden, W.heads, W.ffn_hidden, Lp, W.rank,
+                                     seed=1000, iid=True)
+    ref = oracle_pruned(x, k, w, W.heads, Kp, Vp, Wc, Gc)
+    blk = GpuBlock(W.hidden, W.heads, W.ffn_hidden, "f32", w, Kp, Vp, W.total_len(), scales=W.scales)
+    xd = to_dev(x, "f32")
+    s, keep, drop = blk.score_select(xd, k)
+    y_keep = blk.pruned(xd, keep, k)
+    y = blk.fill(y_keep, keep, drop, M, to_dev(Wc, "f32"), to_dev(Gc, "f32"))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(s), ref["scores"])
+    assert np.array_equal(keep.cpu().numpy(), ref["idx_keep"])
+    assert np.array_equal(drop.cpu().numpy(), ref["idx_drop"])
+    assert rel_err(to_np(y_keep), ref["y_keep"]) <= 1e-4
+    assert rel_err(to_np(y), ref["y"]) <= 1e-4
+    yd, _, _ = oracle_dense(x, w, W.heads, Kp, Vp)
+    blkd = GpuBlock(W.hidden, W.heads, W.ffn_hidden, "f32", w, Kp, Vp, W.total_len())
+    assert rel_err(to_np(blkd.dense(xd)), yd) <= 1e-4
+
+
+@pytest.mark.parametrize("side", [24, 32])
+def test_var_d30_full_batch_launch_shape(side):
+    """The benchmark's launch configuration (batch 8, hidden 1920, 30 heads).  One sample is
+    compared element by element with the oracle; the others through properties that hold at any
+    size (partition, scatter copies, fill rows against the plain product)."""
+    W = wl.WORKLOADS["var_d30_512_bf16"]
+    B, d, H, F, r = W.batch, W.hidden, W.heads, W.ffn_hidden, W.rank
+    M, Lp, k = W.tokens(side), W.prev_len(side), W.keep(side)
+    bf = True
+    x = wl.activations_lowrank(B, M, d, seed=1002, bf16=bf)
+    w = wl.block_weights(d, F, seed=2000, bf16=bf)
+    Kp, Vp = wl.kv_prefix(B, Lp, H, d // H, seed=3000, bf16=bf)
+    Wc, Gc = wl.direct_factors(B, M, r, d, seed=4000, bf16=bf)
+    blk = GpuBlock(d, H, F, "bf16", w, Kp, Vp, W.total_len(), scales=W.scales)
+    xd = to_dev(x, "bf16")
+    s, keep, drop = blk.score_select(xd, k)
+    y_keep = blk.pruned(xd, keep, k)
+    y = blk.fill(y_keep, keep, drop, M, to_dev(Wc, "bf16"), to_dev(Gc, "bf16"))
+    torch.cuda.synchronize()
+    keep_h, drop_h, y_h, yk_h = keep.cpu().numpy(), drop.cpu().numpy(), to_np(y), to_np(y_keep)
+    rng = np.random.default_rng(side)
+    for b in range(B):
+        so = oracle.scores(x[b])
+        assert np.array_equal(to_np(s[b]), so)
+        ko, do = oracle.topk(so, k)
+        assert np.array_equal(keep_h[b], ko) and np.array_equal(drop_h[b], do)
+        assert np.array_equal(y_h[b][keep_h[b]], yk_h[b])
+        rows = rng.choice(drop_h[b], 16, replace=False)
+        ref_rows = Wc[b][rows].astype(np.float64) @ Gc[b].astype(np.float64)
+        assert rel_err(y_h[b][rows], ref_rows) <= 2e-2
+    b = 5
+    ref = oracle_pruned(x[b:b + 1], k, w, H, Kp[b:b + 1], Vp[b:b + 1], Wc[b:b + 1], Gc[b:b + 1])
+    assert rel_err(to_np(blk.K[b, Lp:Lp + k]), ref["K_new"][0]) <= 2e-2
+    assert rel_err(yk_h[b], ref["y_keep"][0]) <= 2e-2
+    assert rel_err(y_h[b], ref["y"][0]) <= 2e-2
