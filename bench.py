@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Benchmark of the late-scale pruned block path on one MI355X.
+
+A step = both late scales of the VAR-d30-shaped 512 px workload (24x24 and 32x32 tokens, batch 8,
+hidden 1920, 30 heads) through all 30 blocks; every block runs score -> select -> pruned block
+(gather, LN, QKV, attention over the multi-scale cache, O, LN, MLP) -> low-rank fill + scatter,
+and its output token map is the next block's input.  Inputs are synthetic and resident in HBM.
+Prints one JSON line."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+WORKLOAD = "var_d30_512_bf16"
+
+
+class Chain:
+    """Device state of one workload and the launch sequence of one step."""
+
+    def __init__(self, W, fv, torch):
+        import workloads as wl
+        self.W, self.fv, self.torch = W, fv, torch
+        self.ctx = fv.Context(hidden=W.hidden, heads=W.heads, head_dim=W.head_dim,
+                              ffn_hidden=W.ffn_hidden, scales=W.scales, dtype=W.dtype)
+        self.blocks = wl.device_block_state(W)
+        self.cap = W.total_len()
+        self.scale = {}
+        dt = torch.bfloat16 if W.dtype == "bf16" else torch.float32
+        B, d = W.batch, W.hidden
+        for side in W.late_scales:
+            M, k = W.tokens(side), W.keep(side)
+            x0, Wc, Gc = wl.device_workload(W, side)
+            self.scale[side] = dict(
+                M=M, k=k, Lp=W.prev_len(side), x0=x0, Wc=Wc, Gc=Gc,
+                bufs=[torch.empty((B, M, d), dtype=dt, device="cuda") for _ in range(2)],
+                y_keep=torch.empty((B, k, d), dtype=dt, device="cuda"),
+                keep=torch.empty((B, k), dtype=torch.int32, device="cuda"),
+                drop=torch.empty((B, M - k), dtype=torch.int32, device="cuda"))
+        maxM = max(s["M"] for s in self.scale.values())
+        self.sel_ws = torch.empty(fv.fvar_select_workspace_bytes(self.ctx, B, maxM),
+                                  dtype=torch.uint8, device="cuda")
+        self.ws = torch.empty(fv.fvar_block_workspace_bytes(self.ctx, B, maxM), dtype=torch.uint8,
+                              device="cuda")
+
+    def pruned_scale(self, side):
+        fv, W, s = self.fv, self.W, self.scale[side]
+        B, M, k, r = W.batch, s["M"], s["k"], W.rank
+        x = s["x0"]
+        for i, (w, K, V) in enumerate(self.blocks):
+            y = s["bufs"][i & 1]
+            fv.fvar_score_select(self.ctx, x, B, M, k, s["keep"], s["drop"], ws=self.sel_ws)
+            fv.fvar_block_forward_pruned(self.ctx, w, x, B, M, s["keep"], k, K, V, self.cap, s["Lp"],
+                                         s["y_keep"], self.ws)
+            fv.fvar_lowrank_fill(self.ctx, s["y_keep"], s["keep"], s["drop"], B, M, k, r,
+                                 s["Wc"][i], s["Gc"][i], y)
+            x = y
+        return x
+
+    def dense_scale(self, side):
+        fv, W, s = self.fv, self.W, self.scale[side]
+        B, M = W.batch, s["M"]
+        x = s["x0"]
+        for i, (w, K, V) in enumerate(self.blocks):
+            y = s["bufs"][i & 1]
+            fv.fvar_block_forward_dense(self.ctx, w, x, B, M, K, V, self.cap, s["Lp"], y, self.ws)
+            x = y
+        return x
+
+    def step(self, dense=False, events=None):
+        for side in self.W.late_scales:
+            if events is not None:
+                e0 = self.torch.cuda.Event(enable_timing=True)
+                e1 = self.torch.cuda.Event(enable_timing=True)
+                e0.record()
+            (self.dense_scale if dense else self.pruned_scale)(side)
+            if events is not None:
+                e1.record()
+                events.setdefault(side, []).append((e0, e1))
+
+
+def gemm_flops(W, side, dense=False):
+    """Algorithmic flops of the four linear layers of one block launch set: 24 * rows * d^2."""
+    rows = W.batch * (W.tokens(side) if dense else W.keep(side))
+    d, F = W.hidden, W.ffn_hidden
+    return {"gemm_qkv": 2.0 * rows * 3 * d * d, "gemm_o": 2.0 * rows * d * d,
+            "gemm_fc1": 2.0 * rows * F * d, "gemm_fc2": 2.0 * rows * d * F}
+
+
+def kernel_work(W, side):
+    """Algorithmic work of one launch of every kernel label at scale `side` (pruned path):
+    (kind, amount) with kind 'flop' or 'byte'."""
+    es = 2 if W.dtype == "bf16" else 4
+    B, M, k, d, r = W.batch, W.tokens(side), W.keep(side), W.hidden, W.rank
+    L = W.prev_len(side) + k
+    out = {lab: ("flop", v) for lab, v in gemm_flops(W, side).items()}
+    out["attention"] = ("flop", 4.0 * B * k * L * d)
+    out["score"] = ("byte", B * M * (d * es + 4.0))
+    out["select"] = ("byte", B * M * 8.0)
+    out["gather_ln1"] = ("byte", B * k * (3.0 * d * es + 4))
+    out["ln2"] = ("byte", B * k * 2.0 * d * es)
+    out["fill"] = ("byte", B * (M * d * es + k * d * es + (M - k) * r * es + r * d * es))
+    return out
+
+
+def cpu_baseline(W):
+    """The CPU oracle on a bounded sample: one block, one batch element, both late scales."""
+    import numpy as np
+    import oracle
+    import workloads as wl
+    d, H, F, r = W.hidden, W.heads, W.ffn_hidden, W.rank
+    w = oracle.BlockWeights(**wl.block_weights(d, F, seed=2000, bf16=True))
+    tokens, secs = 0, 0.0
+    for side in W.late_scales:
+        M, k, Lp = W.tokens(side), W.keep(side), W.prev_len(side)
+        x = wl.activations_lowrank(1, M, d, seed=1000 + side, bf16=True)[0]
+        Kp, Vp = wl.kv_prefix(1, Lp, H, d // H, seed=3000, bf16=True)
+        Wc, Gc = wl.direct_factors(1, M, r, d, seed=4000, bf16=True)
+        Kc = np.zeros((Lp + k, H, d // H), np.float32)
+        Vc = np.zeros_like(Kc)
+        Kc[:Lp], Vc[:Lp] = Kp[0], Vp[0]
+        t0 = time.perf_counter()
+        oracle.pruned_step(x, k, w, H, Kc, Vc, Lp, Wc[0], Gc[0])
+        secs += time.perf_counter() - t0
+        tokens += M
+    per_block_sample = secs
+    return {"value": tokens / (per_block_sample * W.blocks), "unit": "tokens/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"1 of {W.blocks} blocks x 1 of {W.batch} samples, scales "
+                      f"{'+'.join(str(s) for s in W.late_scales)} ({secs:.2f} s measured); value = "
+                      f"sample tokens / (sample time x {W.blocks} blocks), i.e. extrapolated to the "
+                      "full depth"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this path has no multi-GPU part (run with --gpus 1)")
+
+    import torch
+    import paper_2512_16483_amd as fv
+    import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    W = wl.WORKLOADS[WORKLOAD]
+    chain = Chain(W, fv, torch)
+
+    for _ in range(args.warmup):
+        chain.step()
+    torch.cuda.synchronize()
+    events = {}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        chain.step(events=events)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    tokens = W.batch * sum(W.tokens(s) for s in W.late_scales)
+    ms_scale = {str(s): sum(a.elapsed_time(b) for a, b in ev) / len(ev) for s, ev in events.items()}
+
+    # dense control, same chain without the reduction
+    dense = None
+    if not args.no_dense:
+        chain.step(dense=True)
+        torch.cuda.synchronize()
+        dev = {}
+        n = max(2, args.steps // 3)
+        t0 = time.perf_counter()
+        for _ in range(n):
+            chain.step(dense=True, events=dev)
+        torch.cuda.synchronize()
+        d_ms = (time.perf_counter() - t0) * 1e3 / n
+        dense = {"ms_per_step": d_ms, "tokens_per_s": tokens / (d_ms * 1e-3),
+                 "ms_per_scale": {str(s): sum(a.elapsed_time(b) for a, b in ev) / len(ev)
+                                  for s, ev in dev.items()}}
+
+    # per-kernel durations: HIP event pairs recorded by the library on the launch stream
+    prof_steps = 2
+    per_scale = {}
+    fv.fvar_profile_enable(chain.ctx, True)
+    for side in W.late_scales:
+        for _ in range(prof_steps):
+            chain.pruned_scale(side)
+        torch.cuda.synchronize()
+        per_scale[side] = fv.fvar_profile_read(chain.ctx)
+    fv.fvar_profile_enable(chain.ctx, False)
+
+    kernels = {}
+    for side, prof in per_scale.items():
+        work = kernel_work(W, side)
+        for lab, (launches, total_ms) in prof.items():
+            kind, amount = work[lab]
+            e = kernels.setdefault(lab, {"launches": 0, "total_ms": 0.0, "work": 0.0, "kind": kind})
+            e["launches"] += launches
+            e["total_ms"] += total_ms
+            e["work"] += amount * launches
+    report = {}
+    for lab, e in kernels.items():
+        avg_us = e["total_ms"] * 1e3 / e["launches"]
+        rate = e["work"] / (e["total_ms"] * 1e-3)
+        if e["kind"] == "flop":
+            report[lab] = {"avg_us": round(avg_us, 2), "TFLOP/s": round(rate / 1e12, 1),
+                           "frac_of_mfma_peak": round(rate / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+        else:
+            report[lab] = {"avg_us": round(avg_us, 2), "GB/s": round(rate / 1e9, 1),
+                           "frac_of_hbm_peak": round(rate / 1e9 / HBM_PEAK_GBS, 4)}
+    # the four linear layers are one kernel (same code, four shapes): the dominant one
+    gl = [l for l in kernels if l.startswith("gemm_")]
+    g_ms = sum(kernels[l]["total_ms"] for l in gl)
+    g_flop = sum(kernels[l]["work"] for l in gl)
+    g_launch = sum(kernels[l]["launches"] for l in gl)
+    total_ms = sum(e["total_ms"] for e in kernels.values())
+    achieved = g_flop / (g_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (qkv, o, fc1, fc2 launches)",
+                "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "avg_launch_us": round(g_ms * 1e3 / g_launch, 2),
+                "flop_per_launch": g_flop / g_launch,
+                "share_of_kernel_time": round(g_ms / total_ms, 3)}
+
+    out = {
+        "metric": "late-scale pruned block throughput (tokens/s; ms per late scale in ms_per_scale)",
+        "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": W.dtype,
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD, "hidden": W.hidden, "heads": W.heads,
+                   "head_dim": W.head_dim, "blocks": W.blocks, "batch": W.batch,
+                   "late_scales": list(W.late_scales), "keep_ratio": W.keep_num / W.keep_den,
+                   "rank": W.rank, "kv_tokens": W.total_len()},
+        "ms_per_scale": ms_scale,
+        "dense_control": dense,
+        "speedup_vs_dense": (dense["ms_per_step"] / ms_per_step) if dense else None,
+        "roofline": roofline,
+        "kernels": report,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(W)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

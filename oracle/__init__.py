@@ -224,3 +224,8 @@ def keep_count(M: int, num: int, den: int) -> int:
     """k = ceil(M*num/den) in integer arithmetic, clamped to [1, M]."""
     k = -((-M * num) // den)
     return max(1, min(M, k))
+
+
+def num_threads() -> int:
+    """OpenMP threads the C loops run on."""
+    return int(_load().fvo_num_threads())

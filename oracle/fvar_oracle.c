@@ -272,3 +272,11 @@ void fvo_pruned_step(const float *x, int M, int k, int d, int H, int Dh, int F, 
     fvo_lowrank_fill(y_keep, keep, drop, M, k, d, r, Wc, Gc, Y);
     free(xk);
 }
+
+/* Number of OpenMP threads the loops above use (reported next to oracle timings). */
+#ifdef _OPENMP
+#include <omp.h>
+int fvo_num_threads(void) { return omp_get_max_threads(); }
+#else
+int fvo_num_threads(void) { return 1; }
+#endif

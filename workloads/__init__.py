@@ -167,3 +167,46 @@ def direct_factors(B: int, M: int, r: int, d: int, seed: int = 4000, bf16: bool 
     W = _q(g.standard_normal((B, M, r)), bf16)
     G = _q(g.standard_normal((B, r, d)) / np.sqrt(r), bf16)
     return W, G
+
+
+# --------------------------------------------------------------------------- device-side generators
+# Same recipes as above, drawn with torch's seeded generator directly in GPU memory: the
+# throughput workloads hold gigabytes of weights and caches, too much to draw on the host.
+def device_workload(W: Workload, side: int, seed: int = 1000, device: str = "cuda"):
+    """Synthetic device tensors of one late scale of workload W (torch tensors, W.dtype):
+    x0[B,M,d] (low rank + noise, log-normal row scales), per block factors W_c[B,M,r], G_c[B,r,d]."""
+    import torch
+    dt = torch.bfloat16 if W.dtype == "bf16" else torch.float32
+    g = torch.Generator(device=device)
+    g.manual_seed(seed + side)
+    B, M, d, r = W.batch, side * side, W.hidden, W.rank
+    rho = int(np.ceil(0.176 * min(M, d)))
+    A = torch.randn((B, M, rho), generator=g, device=device)
+    Bm = torch.randn((B, d, rho), generator=g, device=device)
+    E = torch.randn((B, M, d), generator=g, device=device)
+    a = torch.exp(0.5 * torch.randn((B, M, 1), generator=g, device=device))
+    x0 = (a * (A @ Bm.transpose(1, 2) / rho ** 0.5 + 0.1 * E)).to(dt).contiguous()
+    Wc = [torch.randn((B, M, r), generator=g, device=device).to(dt) for _ in range(W.blocks)]
+    Gc = [(torch.randn((B, r, d), generator=g, device=device) / r ** 0.5).to(dt)
+          for _ in range(W.blocks)]
+    return x0, Wc, Gc
+
+
+def device_block_state(W: Workload, seed: int = 2000, device: str = "cuda"):
+    """Per block: weights N(0, 0.02^2) (`out,in`, no bias, no affine) and a KV cache
+    [B, total_len, H, Dh] ~ N(0,1) that stands for the keys/values of the earlier scales."""
+    import torch
+    dt = torch.bfloat16 if W.dtype == "bf16" else torch.float32
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    d, F, B, L = W.hidden, W.ffn_hidden, W.batch, W.total_len()
+    blocks = []
+    for _ in range(W.blocks):
+        w = {"w_qkv": (0.02 * torch.randn((3 * d, d), generator=g, device=device)).to(dt),
+             "w_o": (0.02 * torch.randn((d, d), generator=g, device=device)).to(dt),
+             "w_fc1": (0.02 * torch.randn((F, d), generator=g, device=device)).to(dt),
+             "w_fc2": (0.02 * torch.randn((d, F), generator=g, device=device)).to(dt)}
+        K = torch.randn((B, L, W.heads, W.head_dim), generator=g, device=device).to(dt)
+        V = torch.randn((B, L, W.heads, W.head_dim), generator=g, device=device).to(dt)
+        blocks.append((w, K, V))
+    return blocks
