@@ -5,11 +5,13 @@
 // bf16: 256 threads = 4 wavefronts, workgroup tile BM x BN x 64, v_mfma_f32_32x32x16_bf16 with
 // fp32 accumulation.  Tiles are staged global -> registers -> LDS with the next tile's global
 // loads in flight during the current tile's MFMAs (double-buffered LDS, one barrier per k-tile).
-// LDS rows are 128 B; the 16-byte chunk index is XOR-swizzled with the row so that the
-// ds_read_b128 operand fetches of 8 consecutive rows fall into distinct banks.
+// LDS rows are 128 B; the 16-byte chunk index is XOR-swizzled with (row/2)%8 so that the
+// ds_read_b128 operand fetches of 16 consecutive rows cover all 64 banks exactly once.
 // Workgroup ids are remapped so that each XCD (own L2) works on a compact patch of the tile grid.
 //
 // fp32: plain LDS-tiled FMA kernel, used only by the fp32 parity configuration.
+#include <type_traits>
+
 #include "common.h"
 
 namespace fvar {
@@ -50,11 +52,22 @@ constexpr int BK = 64;
 
 __device__ __forceinline__ int lds_off(int row, int chunk)      // in bf16 elements
 {
-    return row * BK + ((chunk ^ (row & 7)) << 3);
+    return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3);
+}
+
+typedef int intx4_t __attribute__((ext_vector_type(4)));
+
+// 16-byte global load whose position in the instruction stream is fixed.  The result must not be
+// read before an explicit s_waitcnt vmcnt (the compiler does not count this load).
+__device__ __forceinline__ intx4_t global_load_b128(const void *base, uint32_t byte_off)
+{
+    intx4_t v;
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(byte_off), "s"(base) : "memory");
+    return v;
 }
 
 template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint16_t *__restrict__ A,
+__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t *__restrict__ A,
                                                         const uint16_t *__restrict__ W, int rows,
                                                         int N, int K, int tiles_m, int tiles_n,
                                                         EpiParams ep)
@@ -86,19 +99,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint16_t *__restri
     const int wm = wave / WN, wn = wave % WN;
 
     // ---- global load assignment (rows beyond the matrix are clamped; their results are masked)
-    const uint16_t *a_src[LA];
-    const uint16_t *b_src[LB];
+    // byte offsets from the (uniform) matrix base: one VGPR per load instead of a 64-bit pointer
+    uint32_t a_src[LA], b_src[LB];
     int a_dst[LA], b_dst[LB];
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         const int id = tid + 256 * i, r = id >> 3, c = id & 7;
-        a_src[i] = A + (size_t)min(row0 + r, rows - 1) * K + c * 8;
+        a_src[i] = (uint32_t)(((size_t)min(row0 + r, rows - 1) * K + c * 8) * sizeof(uint16_t));
         a_dst[i] = lds_off(r, c);
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
         const int id = tid + 256 * i, r = id >> 3, c = id & 7;
-        b_src[i] = W + (size_t)min(col0 + r, N - 1) * K + c * 8;
+        b_src[i] = (uint32_t)(((size_t)min(col0 + r, N - 1) * K + c * 8) * sizeof(uint16_t));
         b_dst[i] = BM * BK + lds_off(r, c);
     }
 
@@ -108,55 +121,68 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint16_t *__restri
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = floatx16_t{0};
 
-    uint4 ra[LA], rb[LB];
+    auto load_frags = [&](const uint16_t *tile, int kk, bf16x8_t *a, bf16x8_t *b) {
 #pragma unroll
-    for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const uint4 *>(a_src[i]);
+        for (int i = 0; i < FM; ++i) {
+            const int r = wm * TM + i * 32 + rl;
+            a[i] = *reinterpret_cast<const bf16x8_t *>(tile + lds_off(r, kk * 2 + g));
+        }
 #pragma unroll
-    for (int i = 0; i < LB; ++i) rb[i] = *reinterpret_cast<const uint4 *>(b_src[i]);
+        for (int j = 0; j < FN; ++j) {
+            const int r = wn * TN + j * 32 + rl;
+            b[j] = *reinterpret_cast<const bf16x8_t *>(tile + BM * BK + lds_off(r, kk * 2 + g));
+        }
+    };
+
+    // Pipeline: while k-tile kt is multiplied out of LDS stage kt%2, tile kt+1 travels global ->
+    // registers -> the other stage.  The loads are issued through asm so that they stay at the
+    // top of the iteration (the compiler would sink them next to the LDS stores otherwise); the
+    // staging registers are written by the asm and read after the explicit vmcnt wait inside the
+    // same straight-line block, so no in-flight register ever crosses a branch.  The last
+    // iteration re-reads its own tile (the copy is never consumed).
+    const int ktiles = K / BK;
+    intx4_t ra[LA], rb[LB];
 #pragma unroll
-    for (int i = 0; i < LA; ++i) *reinterpret_cast<uint4 *>(lds + a_dst[i]) = ra[i];
+    for (int i = 0; i < LA; ++i)
+        ra[i] = *reinterpret_cast<const intx4_t *>(reinterpret_cast<const char *>(A) + a_src[i]);
 #pragma unroll
-    for (int i = 0; i < LB; ++i) *reinterpret_cast<uint4 *>(lds + b_dst[i]) = rb[i];
+    for (int i = 0; i < LB; ++i)
+        rb[i] = *reinterpret_cast<const intx4_t *>(reinterpret_cast<const char *>(W) + b_src[i]);
+#pragma unroll
+    for (int i = 0; i < LA; ++i) *reinterpret_cast<intx4_t *>(lds + a_dst[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < LB; ++i) *reinterpret_cast<intx4_t *>(lds + b_dst[i]) = rb[i];
     __syncthreads();
 
-    const int ktiles = K / BK;
     for (int kt = 0; kt < ktiles; ++kt) {
         const uint16_t *cur = lds + (kt & 1) * STAGE;
         uint16_t *nxt = lds + ((kt + 1) & 1) * STAGE;
-        const bool more = kt + 1 < ktiles;
-        if (more) {
-            const int koff = (kt + 1) * BK;
+        const int koff = min(kt + 1, ktiles - 1) * BK;
 #pragma unroll
-            for (int i = 0; i < LA; ++i) ra[i] = *reinterpret_cast<const uint4 *>(a_src[i] + koff);
+        for (int i = 0; i < LA; ++i) ra[i] = global_load_b128(A + koff, a_src[i]);
 #pragma unroll
-            for (int i = 0; i < LB; ++i) rb[i] = *reinterpret_cast<const uint4 *>(b_src[i] + koff);
-        }
+        for (int i = 0; i < LB; ++i) rb[i] = global_load_b128(W + koff, b_src[i]);
+        __builtin_amdgcn_sched_barrier(0);
+        // operand fragments run one 16-wide k-step ahead of the MFMAs that consume them
+        bf16x8_t af[2][FM], bfr[2][FN];
+        load_frags(cur, 0, af[0], bfr[0]);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8_t af[FM], bfr[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                const int r = wm * TM + i * 32 + rl;
-                af[i] = *reinterpret_cast<const bf16x8_t *>(cur + lds_off(r, kk * 2 + g));
-            }
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int r = wn * TN + j * 32 + rl;
-                bfr[j] = *reinterpret_cast<const bf16x8_t *>(cur + BM * BK + lds_off(r, kk * 2 + g));
-            }
+            if (kk + 1 < BK / 16) load_frags(cur, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0,
-                                                                        0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j],
+                                                                        acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the asm loads above have landed
 #pragma unroll
-            for (int i = 0; i < LA; ++i) *reinterpret_cast<uint4 *>(nxt + a_dst[i]) = ra[i];
+        for (int i = 0; i < LA; ++i) *reinterpret_cast<intx4_t *>(nxt + a_dst[i]) = ra[i];
 #pragma unroll
-            for (int i = 0; i < LB; ++i) *reinterpret_cast<uint4 *>(nxt + b_dst[i]) = rb[i];
-        }
+        for (int i = 0; i < LB; ++i) *reinterpret_cast<intx4_t *>(nxt + b_dst[i]) = rb[i];
         __syncthreads();
     }
 
