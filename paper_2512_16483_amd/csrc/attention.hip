@@ -21,6 +21,17 @@ namespace fvar {
 
 constexpr int BT = 64;                       // keys per tile
 
+typedef int intx4_t __attribute__((ext_vector_type(4)));
+
+// 16-byte global load whose position in the instruction stream is fixed.  The result must not be
+// read before an explicit s_waitcnt vmcnt (the compiler does not count this load).
+__device__ __forceinline__ intx4_t global_load_b128(const void *base, uint32_t byte_off)
+{
+    intx4_t v;
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(byte_off), "s"(base) : "memory");
+    return v;
+}
+
 template <int DH, int NQ>
 __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restrict__ q,
                                                         const uint16_t *__restrict__ Kc,
@@ -33,7 +44,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
     constexpr int KCH = DH / 8;              // 16 B chunks per K row
     constexpr int LK = BT * KCH / 256;       // K chunks per thread per tile
     constexpr int VBLK = (BT / 4) * (DH / 8);        // 4x8 transpose blocks per V tile
-    constexpr int LV = (VBLK + 255) / 256;
+    constexpr int LV = (VBLK + 255) / 256;       // V blocks per thread
     constexpr int KTILE = BT * DH, STAGE = 2 * KTILE;
 
     extern __shared__ uint4 lds_raw[];
@@ -69,61 +80,58 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
     // V block: 4 key rows x 8 head-dim columns.  tb4 = 2*chunk + half; chunk = 2*w + gg covers
     // keys 16w + 8a + 4gg + jj (a = half, jj = 0..3): the order in which a lane's accumulator
     // entries enumerate the keys of a 16-key MFMA step.
+    // When the tile has fewer blocks than threads (head_dim 64) the upper threads repeat the
+    // lower ones' blocks: same loads, same LDS stores, no divergence.
     int v_t0[LV], v_col[LV], v_dst[LV];
-    bool v_on[LV];
 #pragma unroll
     for (int i = 0; i < LV; ++i) {
-        const int blk = tid + 256 * i;
-        v_on[i] = blk < VBLK;
-        const int cb = blk % (DH / 8), tb4 = (blk / (DH / 8)) % (BT / 4);
+        const int blk = (tid + 256 * i) % VBLK;
+        const int cb = blk % (DH / 8), tb4 = blk / (DH / 8);
         const int chunk = tb4 >> 1, a = tb4 & 1, w = chunk >> 1, gg = chunk & 1;
         v_t0[i] = 16 * w + 8 * a + 4 * gg;
         v_col[i] = cb * 8;
         v_dst[i] = chunk * 8 + a * 4;        // element offset inside an unswizzled V^T row
     }
 
-    uint4 kreg[LK];
-    uint4 vreg[LV][4];
+    // The tile loads are issued through asm so that they stay where they are written (the
+    // compiler would sink them next to the LDS stores); their registers are read only after the
+    // explicit vmcnt wait further down the same straight-line block.
+    intx4_t kreg[LK];
+    intx4_t vreg[LV][4];
     auto load_tile = [&](int t0) {
 #pragma unroll
         for (int i = 0; i < LK; ++i) {
             const int t = min(t0 + k_row[i], L - 1);
-            kreg[i] = *reinterpret_cast<const uint4 *>(Kb + (size_t)t * rowpitch + k_chk[i] * 8);
+            kreg[i] = global_load_b128(Kb, (uint32_t)(((size_t)t * rowpitch + k_chk[i] * 8) * 2));
         }
 #pragma unroll
         for (int i = 0; i < LV; ++i) {
-            if (!v_on[i]) continue;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
                 const int t = min(t0 + v_t0[i] + jj, L - 1);
-                vreg[i][jj] = *reinterpret_cast<const uint4 *>(Vb + (size_t)t * rowpitch + v_col[i]);
+                vreg[i][jj] = global_load_b128(Vb, (uint32_t)(((size_t)t * rowpitch + v_col[i]) * 2));
             }
         }
     };
     auto store_tile = [&](uint16_t *st) {
 #pragma unroll
         for (int i = 0; i < LK; ++i)
-            *reinterpret_cast<uint4 *>(st + k_row[i] * DH + ((k_chk[i] ^ (k_row[i] & 7)) << 3)) =
+            *reinterpret_cast<intx4_t *>(st + k_row[i] * DH + ((k_chk[i] ^ ((k_row[i] >> 1) & 7)) << 3)) =
                 kreg[i];
         uint16_t *vt = st + KTILE;
 #pragma unroll
         for (int i = 0; i < LV; ++i) {
-            if (!v_on[i]) continue;
-            const uint32_t *w0 = reinterpret_cast<const uint32_t *>(&vreg[i][0]);
-            const uint32_t *w1 = reinterpret_cast<const uint32_t *>(&vreg[i][1]);
-            const uint32_t *w2 = reinterpret_cast<const uint32_t *>(&vreg[i][2]);
-            const uint32_t *w3 = reinterpret_cast<const uint32_t *>(&vreg[i][3]);
             const int chunk = v_dst[i] >> 3, sub = v_dst[i] & 7;
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 uint2 lo, hi;
-                lo.x = __builtin_amdgcn_perm(w1[m], w0[m], 0x05040100u);
-                lo.y = __builtin_amdgcn_perm(w3[m], w2[m], 0x05040100u);
-                hi.x = __builtin_amdgcn_perm(w1[m], w0[m], 0x07060302u);
-                hi.y = __builtin_amdgcn_perm(w3[m], w2[m], 0x07060302u);
+                lo.x = __builtin_amdgcn_perm(vreg[i][1][m], vreg[i][0][m], 0x05040100u);
+                lo.y = __builtin_amdgcn_perm(vreg[i][3][m], vreg[i][2][m], 0x05040100u);
+                hi.x = __builtin_amdgcn_perm(vreg[i][1][m], vreg[i][0][m], 0x07060302u);
+                hi.y = __builtin_amdgcn_perm(vreg[i][3][m], vreg[i][2][m], 0x07060302u);
                 const int d0 = v_col[i] + 2 * m, d1 = d0 + 1;
-                *reinterpret_cast<uint2 *>(vt + d0 * BT + ((chunk ^ (d0 & 7)) << 3) + sub) = lo;
-                *reinterpret_cast<uint2 *>(vt + d1 * BT + ((chunk ^ (d1 & 7)) << 3) + sub) = hi;
+                *reinterpret_cast<uint2 *>(vt + d0 * BT + ((chunk ^ ((d0 >> 1) & 7)) << 3) + sub) = lo;
+                *reinterpret_cast<uint2 *>(vt + d1 * BT + ((chunk ^ ((d1 >> 1) & 7)) << 3) + sub) = hi;
             }
         }
     };
@@ -138,6 +146,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
     for (int j = 0; j < NQ; ++j) { m_run[j] = -INFINITY; l_run[j] = 0.f; }
 
     load_tile(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     store_tile(lds);
     __syncthreads();
 
@@ -145,8 +154,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
     for (int it = 0; it < ntiles; ++it) {
         const uint16_t *ks = lds + (it & 1) * STAGE;
         const uint16_t *vt = ks + KTILE;
-        const bool more = it + 1 < ntiles;
-        if (more) load_tile((it + 1) * BT);
+        // next tile (row indices are clamped, so the request past the end is harmless)
+        load_tile((it + 1) * BT);
+        __builtin_amdgcn_sched_barrier(0);
 
         // ---- S^T = K Q^T : [64 keys] x [32*NQ queries]
         floatx16_t sacc[2][NQ];
@@ -160,7 +170,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
             for (int tb = 0; tb < 2; ++tb) {
                 const int r = tb * 32 + rl;
                 const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(
-                    ks + r * DH + (((2 * s + g) ^ (r & 7)) << 3));
+                    ks + r * DH + (((2 * s + g) ^ ((r >> 1) & 7)) << 3));
 #pragma unroll
                 for (int j = 0; j < NQ; ++j)
                     sacc[tb][j] =
@@ -192,7 +202,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[tb][j][i]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             const float m_new = fmaxf(m_run[j], mx);
-            const float alpha = exp2f((m_run[j] - m_new) * c_log2);
+            const float alpha = __builtin_amdgcn_exp2f((m_run[j] - m_new) * c_log2);
             const float mc = m_new * c_log2;
             m_run[j] = m_new;
             float psum = 0.f;
@@ -201,7 +211,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
                 float p[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    p[i] = exp2f(fmaf(sacc[tb][j][i], c_log2, -mc));
+                    p[i] = __builtin_amdgcn_exp2f(fmaf(sacc[tb][j][i], c_log2, -mc));
                     psum += p[i];
                 }
 #pragma unroll
@@ -215,10 +225,12 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
                 }
             }
             l_run[j] = l_run[j] * alpha + psum;
+            if (__any(alpha != 1.0f)) {                       // wave-uniform: the max rarely moves
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[db][j][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) oacc[db][j][i] *= alpha;
+            }
         }
         // ---- O^T += V^T P^T
 #pragma unroll
@@ -227,14 +239,15 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
             for (int db = 0; db < DB; ++db) {
                 const int dr = db * 32 + rl;
                 const bf16x8_t vf = *reinterpret_cast<const bf16x8_t *>(
-                    vt + dr * BT + (((2 * u + g) ^ (dr & 7)) << 3));
+                    vt + dr * BT + (((2 * u + g) ^ ((dr >> 1) & 7)) << 3));
 #pragma unroll
                 for (int j = 0; j < NQ; ++j)
                     oacc[db][j] =
                         __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u][j], oacc[db][j], 0, 0, 0);
             }
         }
-        if (more) store_tile(lds + ((it + 1) & 1) * STAGE);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the asm loads above have landed
+        store_tile(lds + ((it + 1) & 1) * STAGE);
         __syncthreads();
     }
 
@@ -365,8 +378,8 @@ void launch_attention(DType dt, const void *q, const void *K, const void *V, int
             if (wide) launch_attn_bf16<64, 2>(q, K, V, B, n, L, cap, H, scale, o, st);
             else launch_attn_bf16<64, 1>(q, K, V, B, n, L, cap, H, scale, o, st);
         } else {
-            if (wide) launch_attn_bf16<128, 2>(q, K, V, B, n, L, cap, H, scale, o, st);
-            else launch_attn_bf16<128, 1>(q, K, V, B, n, L, cap, H, scale, o, st);
+            // head_dim 128 with two query blocks per wavefront does not fit the register file
+            launch_attn_bf16<128, 1>(q, K, V, B, n, L, cap, H, scale, o, st);
         }
     } else {
         dim3 grid((n + 31) / 32, H, B), block(256);
