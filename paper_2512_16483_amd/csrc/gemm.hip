@@ -2,12 +2,16 @@
 // MLP): C = epilogue(A[rows,K] * W[N,K]^T).  Both operands are K-contiguous ("out,in" weights),
 // which is the layout the MFMA operands want: a lane holds 8 consecutive k of one row.
 //
-// bf16: 256 threads = 4 wavefronts, workgroup tile BM x BN x 64, v_mfma_f32_32x32x16_bf16 with
-// fp32 accumulation.  Tiles are staged global -> registers -> LDS with the next tile's global
-// loads in flight during the current tile's MFMAs (double-buffered LDS, one barrier per k-tile).
-// LDS rows are 128 B; the 16-byte chunk index is XOR-swizzled with (row/2)%8 so that the
-// ds_read_b128 operand fetches of 16 consecutive rows cover all 64 banks exactly once.
-// Workgroup ids are remapped so that each XCD (own L2) works on a compact patch of the tile grid.
+// bf16: workgroup tile BM x BN x 64 computed by WM x WN wavefronts with v_mfma_f32_32x32x16_bf16
+// (fp32 accumulation).  Tiles are DMA-ed global -> LDS (no register staging) into a ring of
+// stages ahead of the MFMAs; operand fragments are read one 16-wide k-step ahead of the MFMAs
+// that use them.  LDS rows are 128 B; the 16-byte chunk index is XOR-swizzled with (row/2)%8 so
+// that the ds_read_b128 operand fetches of 16 consecutive rows cover all 64 banks exactly once.
+// Workgroup ids are remapped so that each XCD (own L2) works on a compact patch of the tile
+// grid.  Bigger tiles cut the L1/LDS traffic per flop (a 128x128 tile needs the full 64 B/clk of
+// the CU's vector L1 at peak MFMA rate, a 256x256 tile half of it) but quantise badly on the few
+// thousand rows of a pruned scale, so the launcher picks the tile per problem with a small cost
+// model.
 //
 // fp32: plain LDS-tiled FMA kernel, used only by the fp32 parity configuration.
 #include <type_traits>
@@ -55,146 +59,20 @@ __device__ __forceinline__ int lds_off(int row, int chunk)      // in bf16 eleme
     return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3);
 }
 
-typedef int intx4_t __attribute__((ext_vector_type(4)));
-
-// 16-byte global load whose position in the instruction stream is fixed.  The result must not be
-// read before an explicit s_waitcnt vmcnt (the compiler does not count this load).
-__device__ __forceinline__ intx4_t global_load_b128(const void *base, uint32_t byte_off)
+// Epilogue shared by the bf16 kernels.  Accumulator entry e of a 32x32 tile holds row
+// 8*(e/4) + 4*(lane/32) + e%4, column lane%32.  Adjacent lanes swap one value per row pair so
+// that every lane stores two neighbouring columns of one row as a single dword.
+template <int FM, int FN>
+__device__ __forceinline__ void store_tile_epilogue(floatx16_t (&acc)[FM][FN], const EpiParams &ep,
+                                                    int rows, int N, int wrow0, int wcol0, int lane)
 {
-    intx4_t v;
-    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(byte_off), "s"(base) : "memory");
-    return v;
-}
-
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t *__restrict__ A,
-                                                        const uint16_t *__restrict__ W, int rows,
-                                                        int N, int K, int tiles_m, int tiles_n,
-                                                        EpiParams ep)
-{
-    static_assert(WM * WN == 4, "four wavefronts");
-    constexpr int TM = BM / WM, TN = BN / WN;       // wavefront tile
-    constexpr int FM = TM / 32, FN = TN / 32;       // 32x32 MFMA tiles per wavefront
-    constexpr int LA = BM * 8 / 256, LB = BN * 8 / 256;   // 16 B chunks per thread per tile
-    extern __shared__ uint4 lds_raw[];
-    uint16_t *lds = reinterpret_cast<uint16_t *>(lds_raw);
-    // layout: [stage][A tile | B tile]
-    constexpr int STAGE = (BM + BN) * BK;
-
-    // ---- workgroup -> tile: XCD-contiguous ranges, then grouped rows
-    const int ntiles = tiles_m * tiles_n;
-    const int per_xcd = (gridDim.x + 7) / 8;
-    int pid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (pid >= ntiles) return;
-    constexpr int GROUP_M = 8;
-    const int group = pid / (GROUP_M * tiles_n);
-    const int first_m = group * GROUP_M;
-    const int gsize = min(tiles_m - first_m, GROUP_M);
-    const int tm = first_m + (pid % (GROUP_M * tiles_n)) % gsize;
-    const int tn = (pid % (GROUP_M * tiles_n)) / gsize;
-    const int row0 = tm * BM, col0 = tn * BN;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rl = lane & 31, g = lane >> 5;
-    const int wm = wave / WN, wn = wave % WN;
-
-    // ---- global load assignment (rows beyond the matrix are clamped; their results are masked)
-    // byte offsets from the (uniform) matrix base: one VGPR per load instead of a 64-bit pointer
-    uint32_t a_src[LA], b_src[LB];
-    int a_dst[LA], b_dst[LB];
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-        const int id = tid + 256 * i, r = id >> 3, c = id & 7;
-        a_src[i] = (uint32_t)(((size_t)min(row0 + r, rows - 1) * K + c * 8) * sizeof(uint16_t));
-        a_dst[i] = lds_off(r, c);
-    }
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-        const int id = tid + 256 * i, r = id >> 3, c = id & 7;
-        b_src[i] = (uint32_t)(((size_t)min(col0 + r, N - 1) * K + c * 8) * sizeof(uint16_t));
-        b_dst[i] = BM * BK + lds_off(r, c);
-    }
-
-    floatx16_t acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = floatx16_t{0};
-
-    auto load_frags = [&](const uint16_t *tile, int kk, bf16x8_t *a, bf16x8_t *b) {
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int r = wm * TM + i * 32 + rl;
-            a[i] = *reinterpret_cast<const bf16x8_t *>(tile + lds_off(r, kk * 2 + g));
-        }
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int r = wn * TN + j * 32 + rl;
-            b[j] = *reinterpret_cast<const bf16x8_t *>(tile + BM * BK + lds_off(r, kk * 2 + g));
-        }
-    };
-
-    // Pipeline: while k-tile kt is multiplied out of LDS stage kt%2, tile kt+1 travels global ->
-    // registers -> the other stage.  The loads are issued through asm so that they stay at the
-    // top of the iteration (the compiler would sink them next to the LDS stores otherwise); the
-    // staging registers are written by the asm and read after the explicit vmcnt wait inside the
-    // same straight-line block, so no in-flight register ever crosses a branch.  The last
-    // iteration re-reads its own tile (the copy is never consumed).
-    const int ktiles = K / BK;
-    intx4_t ra[LA], rb[LB];
-#pragma unroll
-    for (int i = 0; i < LA; ++i)
-        ra[i] = *reinterpret_cast<const intx4_t *>(reinterpret_cast<const char *>(A) + a_src[i]);
-#pragma unroll
-    for (int i = 0; i < LB; ++i)
-        rb[i] = *reinterpret_cast<const intx4_t *>(reinterpret_cast<const char *>(W) + b_src[i]);
-#pragma unroll
-    for (int i = 0; i < LA; ++i) *reinterpret_cast<intx4_t *>(lds + a_dst[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < LB; ++i) *reinterpret_cast<intx4_t *>(lds + b_dst[i]) = rb[i];
-    __syncthreads();
-
-    for (int kt = 0; kt < ktiles; ++kt) {
-        const uint16_t *cur = lds + (kt & 1) * STAGE;
-        uint16_t *nxt = lds + ((kt + 1) & 1) * STAGE;
-        const int koff = min(kt + 1, ktiles - 1) * BK;
-#pragma unroll
-        for (int i = 0; i < LA; ++i) ra[i] = global_load_b128(A + koff, a_src[i]);
-#pragma unroll
-        for (int i = 0; i < LB; ++i) rb[i] = global_load_b128(W + koff, b_src[i]);
-        __builtin_amdgcn_sched_barrier(0);
-        // operand fragments run one 16-wide k-step ahead of the MFMAs that consume them
-        bf16x8_t af[2][FM], bfr[2][FN];
-        load_frags(cur, 0, af[0], bfr[0]);
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            if (kk + 1 < BK / 16) load_frags(cur, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j],
-                                                                        acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the asm loads above have landed
-#pragma unroll
-        for (int i = 0; i < LA; ++i) *reinterpret_cast<intx4_t *>(nxt + a_dst[i]) = ra[i];
-#pragma unroll
-        for (int i = 0; i < LB; ++i) *reinterpret_cast<intx4_t *>(nxt + b_dst[i]) = rb[i];
-        __syncthreads();
-    }
-
-    // ---- epilogue.  Accumulator entry i of a 32x32 tile: row 8*(i/4) + 4*g + i%4, column rl.
-    // Adjacent lanes swap one value per row pair so that every lane stores two neighbouring
-    // columns of one row as a single dword.
     const uint16_t *bias = reinterpret_cast<const uint16_t *>(ep.bias);
     const uint16_t *res = reinterpret_cast<const uint16_t *>(ep.residual);
     const int odd = lane & 1;
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
-        const int col = col0 + wn * TN + j * 32 + rl;
+        const int col = wcol0 + j * 32 + rl;
         const bool col_ok = col < N;
         const float bv = (bias && col_ok) ? bf16_to_f32(bias[col]) : 0.f;
         const int pcol = col - odd;                          // even column of the stored pair
@@ -206,7 +84,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t *__res
                 if (ep.gelu) { v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); }
                 const float send = odd ? v0 : v1;
                 const float recv = __shfl_xor(send, 1);
-                const int rbase = row0 + wm * TM + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+                const int rbase = wrow0 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
                 const int row = rbase + odd;
                 float lo = odd ? recv : v0, hi = odd ? v1 : recv;
                 if (row < rows && col_ok) {
@@ -224,22 +102,148 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t *__res
     }
 }
 
-template <int BM, int BN, int WM, int WN>
+// The operand tiles travel global -> LDS directly (global_load_lds_dwordx4: 16 bytes per lane, a
+// wavefront fills 1 KiB = 8 swizzled rows per instruction) into a ring of STAGES buffers,
+// STAGES-1 k-tiles ahead of the MFMAs.  No staging registers, no LDS store instructions; the
+// loads are counted by hand (vmcnt) because the compiler does not see them.
+// M0 carries the LDS base of the instruction; nothing else in these kernels uses M0 (gfx9+ LDS
+// instructions do not), and it is rewritten before every use.
+__device__ __forceinline__ void dma_b128(const void *base, uint32_t byte_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t *__restrict__ A,
+                                                            const uint16_t *__restrict__ W, int rows,
+                                                            int N, int K, int tiles_m, int tiles_n,
+                                                            EpiParams ep)
+{
+    constexpr int NW = WM * WN;                        // wavefronts per workgroup
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int FM = TM / 32, FN = TN / 32;
+    constexpr int NGA = BM / 8 / NW, NGB = BN / 8 / NW; // 1 KiB groups (8 rows) per wavefront
+    constexpr int NG = NGA + NGB;                      // DMA instructions per lane per k-tile
+    constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
+    extern __shared__ uint4 lds_raw[];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds_raw;
+
+    const int ntiles = tiles_m * tiles_n;
+    const int per_xcd = (gridDim.x + 7) / 8;
+    int pid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (pid >= ntiles) return;
+    constexpr int GROUP_M = 8;
+    const int group = pid / (GROUP_M * tiles_n);
+    const int first_m = group * GROUP_M;
+    const int gsize = min(tiles_m - first_m, GROUP_M);
+    const int tm = first_m + (pid % (GROUP_M * tiles_n)) % gsize;
+    const int tn = (pid % (GROUP_M * tiles_n)) / gsize;
+    const int row0 = tm * BM, col0 = tn * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rl = lane & 31, g = lane >> 5;
+    const int wm = wave / WN, wn = wave % WN;
+
+    // ---- DMA assignment: wavefront w owns the 8-row groups w, w+NW, ... of each tile; lane l of a
+    // group fills physical chunk l%8 of row 8*group + l/8, i.e. it fetches the logical chunk that
+    // the swizzle maps there
+    uint32_t a_off[NGA], b_off[NGB];                   // byte offsets of this lane's 16 B at k = 0
+#pragma unroll
+    for (int i = 0; i < NGA; ++i) {
+        const int r = (wave + NW * i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        a_off[i] = (uint32_t)(((size_t)min(row0 + r, rows - 1) * K + c * 8) * sizeof(uint16_t));
+    }
+#pragma unroll
+    for (int i = 0; i < NGB; ++i) {
+        const int r = (wave + NW * i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        b_off[i] = (uint32_t)(((size_t)min(col0 + r, N - 1) * K + c * 8) * sizeof(uint16_t));
+    }
+    const int ktiles = K / BK;
+    auto issue = [&](int kt, int stage) {               // DMA of k-tile kt (clamped) into `stage`
+        const int koff = min(kt, ktiles - 1) * BK;
+        const uint32_t sbase = lds_base + stage * STAGE_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < NGA; ++i) dma_b128(A + koff, a_off[i], sbase + i * (NW * 1024));
+#pragma unroll
+        for (int i = 0; i < NGB; ++i) dma_b128(W + koff, b_off[i], sbase + BM * BK * 2 + i * (NW * 1024));
+    };
+
+    floatx16_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = floatx16_t{0};
+
+    const uint16_t *lds = reinterpret_cast<const uint16_t *>(lds_raw);
+    auto load_frags = [&](const uint16_t *tile, int kk, bf16x8_t *a, bf16x8_t *b) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int r = wm * TM + i * 32 + rl;
+            a[i] = *reinterpret_cast<const bf16x8_t *>(tile + lds_off(r, kk * 2 + g));
+        }
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int r = wn * TN + j * 32 + rl;
+            b[j] = *reinterpret_cast<const bf16x8_t *>(tile + BM * BK + lds_off(r, kk * 2 + g));
+        }
+    };
+
+    // prologue: STAGES-1 tiles in flight, the first one landed
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue(s, s);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG * (STAGES - 2)) : "memory");
+    __syncthreads();
+
+    int stage = 0;                                       // stage holding k-tile kt
+    for (int kt = 0; kt < ktiles; ++kt) {
+        int wstage = stage + STAGES - 1;
+        if (wstage >= STAGES) wstage -= STAGES;
+        issue(kt + STAGES - 1, wstage);                  // that stage was read in iteration kt-1
+        __builtin_amdgcn_sched_barrier(0);
+        const uint16_t *cur = lds + stage * (STAGE_BYTES / 2);
+        bf16x8_t af[2][FM], bfr[2][FN];
+        load_frags(cur, 0, af[0], bfr[0]);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            if (kk + 1 < BK / 16) load_frags(cur, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j],
+                                                                        acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // k-tile kt+1 has landed once only the newest STAGES-2 tiles' loads are outstanding
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG * (STAGES - 2)) : "memory");
+        __syncthreads();
+        stage = stage + 1 == STAGES ? 0 : stage + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // drain the clamped tail requests
+    store_tile_epilogue<FM, FN>(acc, ep, rows, N, row0 + wm * TM, col0 + wn * TN, lane);
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES>
 static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, int K,
                                  const EpiParams &ep, hipStream_t st)
 {
     const int tiles_m = (rows + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int ntiles = tiles_m * tiles_n;
     const int grid = (ntiles + 7) / 8 * 8;
-    const size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(uint16_t);
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN>;
+    const size_t lds = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, STAGES>;
     static bool attr_set = false;
-    if (!attr_set && lds > 48 * 1024) {
+    if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, (const uint16_t *)A,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, st, (const uint16_t *)A,
                        (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, ep);
 }
 
@@ -308,7 +312,27 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
     ep.rows_per_sample = e.rows_per_sample > 0 ? e.rows_per_sample : 1;
     ep.N = N;
     if (dt == DType::BF16) {
-        launch_gemm_bf16_cfg<128, 128, 2, 2>(A, W, rows, N, K, ep, st);
+        // cost = rounds of workgroups over the 256 CUs (one workgroup per CU at these LDS sizes)
+        // x tile area / sustained rate of the configuration (TFLOP/s measured on large problems)
+        struct Cand { int bm, bn; double rate; };
+        const Cand cands[4] = {{256, 256, 1155.0}, {256, 128, 1045.0}, {128, 256, 1041.0},
+                               {128, 128, 935.0}};
+        int best = 0;
+        double best_cost = 1e300;
+        for (int i = 0; i < 4; ++i) {
+            const long tiles = (long)((rows + cands[i].bm - 1) / cands[i].bm) *
+                               ((N + cands[i].bn - 1) / cands[i].bn);
+            double rate = cands[i].rate;
+            if (i == 3 && tiles > 256) rate = 600.0;       // small tiles pay per round
+            const double cost = (double)((tiles + 255) / 256) * cands[i].bm * cands[i].bn / rate;
+            if (cost < best_cost) { best_cost = cost; best = i; }
+        }
+        switch (best) {
+        case 0: launch_gemm_bf16_cfg<256, 256, 2, 4, 2>(A, W, rows, N, K, ep, st); break;
+        case 1: launch_gemm_bf16_cfg<256, 128, 4, 2, 3>(A, W, rows, N, K, ep, st); break;
+        case 2: launch_gemm_bf16_cfg<128, 256, 2, 4, 3>(A, W, rows, N, K, ep, st); break;
+        default: launch_gemm_bf16_cfg<128, 128, 2, 2, 3>(A, W, rows, N, K, ep, st); break;
+        }
     } else {
         dim3 grid((N + 63) / 64, (rows + 63) / 64), block(256);
         hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, (const float *)A, (const float *)W,
