@@ -15,6 +15,8 @@
 //     LDS is double buffered, one barrier per tile.
 //
 // fp32 kernel: plain tiled FMA version for the fp32 parity configuration.
+#include <type_traits>
+
 #include "common.h"
 
 namespace fvar {
@@ -23,8 +25,9 @@ constexpr int BT = 64;                       // keys per tile
 
 typedef int intx4_t __attribute__((ext_vector_type(4)));
 
-// 16-byte global load whose position in the instruction stream is fixed.  The result must not be
-// read before an explicit s_waitcnt vmcnt (the compiler does not count this load).
+// 16-byte global load whose position in the instruction stream is fixed.  The compiler does not
+// count this load: the destination must be kept alive and unread until an explicit
+// s_waitcnt vmcnt that the later uses are tied to (see wait_tile below).
 __device__ __forceinline__ intx4_t global_load_b128(const void *base, uint32_t byte_off)
 {
     intx4_t v;
@@ -33,7 +36,7 @@ __device__ __forceinline__ intx4_t global_load_b128(const void *base, uint32_t b
 }
 
 template <int DH, int NQ>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restrict__ q,
+__global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(const uint16_t *__restrict__ q,
                                                         const uint16_t *__restrict__ Kc,
                                                         const uint16_t *__restrict__ Vc, int n, int L,
                                                         int cap, int H, float c_log2,
@@ -113,6 +116,18 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
             }
         }
     };
+    // Wait for the asm loads and make every later use of the staging registers depend on that
+    // wait: the empty asm statements "redefine" the registers, so neither the ALU work of the
+    // transpose nor a reuse of the registers can be scheduled while the loads are in flight.
+    auto wait_tile = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < LK; ++i) asm volatile("" : "+v"(kreg[i]));
+#pragma unroll
+        for (int i = 0; i < LV; ++i)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) asm volatile("" : "+v"(vreg[i][jj]));
+    };
     auto store_tile = [&](uint16_t *st) {
 #pragma unroll
         for (int i = 0; i < LK; ++i)
@@ -146,12 +161,20 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
     for (int j = 0; j < NQ; ++j) { m_run[j] = -INFINITY; l_run[j] = 0.f; }
 
     load_tile(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wait_tile();
     store_tile(lds);
+    // the Q fragments are consumed here once so that the compiler's own wait for their loads
+    // sits in front of the loop instead of inside it (where it would also wait for the prefetch)
+#pragma unroll
+    for (int j = 0; j < NQ; ++j)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qf[j][s]));
     __syncthreads();
 
     const int ntiles = (L + BT - 1) / BT;
-    for (int it = 0; it < ntiles; ++it) {
+    // one key tile; MASKED is set only for the last tile, whose ragged tail must not contribute
+    auto tile = [&](int it, auto masked) {
+        constexpr bool MASKED = decltype(masked)::value;
         const uint16_t *ks = lds + (it & 1) * STAGE;
         const uint16_t *vt = ks + KTILE;
         // next tile (row indices are clamped, so the request past the end is harmless)
@@ -178,8 +201,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
             }
         }
         // ---- mask the ragged tail of the cache
-        const int t0 = it * BT;
-        if (t0 + BT > L) {
+        if (MASKED) {
+            const int t0 = it * BT;
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
@@ -246,10 +269,12 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *__restri
                         __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u][j], oacc[db][j], 0, 0, 0);
             }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the asm loads above have landed
+        wait_tile();
         store_tile(lds + ((it + 1) & 1) * STAGE);
         __syncthreads();
-    }
+    };
+    for (int it = 0; it + 1 < ntiles; ++it) tile(it, std::false_type{});
+    tile(ntiles - 1, std::true_type{});
 
     // ---- normalise and store: lane = query, 4 consecutive head-dim values per accumulator group
 #pragma unroll
