@@ -35,8 +35,9 @@ struct EpiParams {
 __device__ __forceinline__ float gelu_tanh(float v)
 {
     // 0.5 v (1 + tanh(u)) = v / (1 + exp(-2u)),  u = sqrt(2/pi) (v + 0.044715 v^3)
-    const float u = 0.7978845608028654f * (v + 0.044715f * v * v * v);
-    return v / (1.0f + __expf(-2.0f * u));
+    // exp(-2u) = exp2(v * (a + b v^2)) with a = -2 sqrt(2/pi) log2(e), b = 0.044715 a
+    const float t = v * fmaf(-0.10294324f, v * v, -2.3022082f);
+    return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
 // destination of element (row, col) in elements from the base pointer it returns
@@ -59,9 +60,11 @@ __device__ __forceinline__ int lds_off(int row, int chunk)      // in bf16 eleme
     return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3);
 }
 
-// Epilogue shared by the bf16 kernels.  Accumulator entry e of a 32x32 tile holds row
+// Epilogue of the bf16 kernel.  Accumulator entry e of a 32x32 tile holds row
 // 8*(e/4) + 4*(lane/32) + e%4, column lane%32.  Adjacent lanes swap one value per row pair so
-// that every lane stores two neighbouring columns of one row as a single dword.
+// that every lane stores two neighbouring columns of one row as a single dword.  Everything that
+// depends only on the row (destination row pointers, the sample a row belongs to) is computed
+// once per row, outside the column loop.
 template <int FM, int FN>
 __device__ __forceinline__ void store_tile_epilogue(floatx16_t (&acc)[FM][FN], const EpiParams &ep,
                                                     int rows, int N, int wrow0, int wcol0, int lane)
@@ -70,32 +73,56 @@ __device__ __forceinline__ void store_tile_epilogue(floatx16_t (&acc)[FM][FN], c
     const uint16_t *bias = reinterpret_cast<const uint16_t *>(ep.bias);
     const uint16_t *res = reinterpret_cast<const uint16_t *>(ep.residual);
     const int odd = lane & 1;
+    const bool routed = ep.split < N;                       // K/V columns go to the cache
+    const float inv_rps = 1.0f / (float)ep.rows_per_sample;
+    float bv[FN];
+    int pcol[FN];
+    bool col_ok[FN];
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
         const int col = wcol0 + j * 32 + rl;
-        const bool col_ok = col < N;
-        const float bv = (bias && col_ok) ? bf16_to_f32(bias[col]) : 0.f;
-        const int pcol = col - odd;                          // even column of the stored pair
+        col_ok[j] = col < N;
+        bv[j] = (bias && col_ok[j]) ? bf16_to_f32(bias[col]) : 0.f;
+        pcol[j] = col - odd;                                 // even column of the stored pair
+    }
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
+    for (int i = 0; i < FM; ++i) {
 #pragma unroll
-            for (int e = 0; e < 16; e += 2) {
-                float v0 = acc[i][j][e] + bv, v1 = acc[i][j][e + 1] + bv;
+        for (int e = 0; e < 16; e += 2) {
+            const int row = wrow0 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3) + odd;
+            const bool row_ok = row < rows;
+            uint16_t *out_row = (uint16_t *)ep.out0 + (size_t)row * ep.ld0;
+            const uint16_t *res_row = res + (size_t)row * N;
+            uint16_t *k_row = nullptr, *v_row = nullptr;
+            if (routed) {
+                // sample index: float estimate, then one exact correction step
+                int b = (int)(((float)row + 0.5f) * inv_rps);
+                int j0 = row - b * ep.rows_per_sample;
+                if (j0 < 0) { --b; j0 += ep.rows_per_sample; }
+                else if (j0 >= ep.rows_per_sample) { ++b; j0 -= ep.rows_per_sample; }
+                const size_t crow = (size_t)b * ep.cap + ep.len + j0;
+                k_row = (uint16_t *)ep.kcache + crow * ep.hd;
+                v_row = (uint16_t *)ep.vcache + crow * ep.hd;
+            }
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                float v0 = acc[i][j][e] + bv[j], v1 = acc[i][j][e + 1] + bv[j];
                 if (ep.gelu) { v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); }
                 const float send = odd ? v0 : v1;
                 const float recv = __shfl_xor(send, 1);
-                const int rbase = wrow0 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                const int row = rbase + odd;
                 float lo = odd ? recv : v0, hi = odd ? v1 : recv;
-                if (row < rows && col_ok) {
+                if (row_ok && col_ok[j]) {
                     if (res) {
-                        const uint32_t rv =
-                            *reinterpret_cast<const uint32_t *>(res + (size_t)row * N + pcol);
+                        const uint32_t rv = *reinterpret_cast<const uint32_t *>(res_row + pcol[j]);
                         lo += bf16_lo(rv);
                         hi += bf16_hi(rv);
                     }
-                    *reinterpret_cast<uint32_t *>(epi_dst<uint16_t>(ep, row, pcol)) =
-                        pack_bf16x2(lo, hi);
+                    uint16_t *dst;
+                    const int c = pcol[j] - ep.split;
+                    if (c < 0) dst = out_row + pcol[j];
+                    else if (c < ep.hd) dst = k_row + c;
+                    else dst = v_row + (c - ep.hd);
+                    *reinterpret_cast<uint32_t *>(dst) = pack_bf16x2(lo, hi);
                 }
             }
         }
