@@ -14,6 +14,7 @@
 // model.
 //
 // fp32: plain LDS-tiled FMA kernel, used only by the fp32 parity configuration.
+#include <cmath>
 #include <type_traits>
 
 #include "common.h"
@@ -61,71 +62,76 @@ __device__ __forceinline__ int lds_off(int row, int chunk)      // in bf16 eleme
 }
 
 // Epilogue of the bf16 kernel.  Accumulator entry e of a 32x32 tile holds row
-// 8*(e/4) + 4*(lane/32) + e%4, column lane%32.  Adjacent lanes swap one value per row pair so
-// that every lane stores two neighbouring columns of one row as a single dword.  Everything that
-// depends only on the row (destination row pointers, the sample a row belongs to) is computed
-// once per row, outside the column loop.
+// 8*(e/4) + 4*(lane/32) + e%4, column lane%32.  Each wavefront applies bias and GELU, packs to
+// bf16 (adjacent lanes swap one value per row pair so that a lane owns two neighbouring columns)
+// and parks its sub-tile row-major in a private LDS region; it then reads the sub-tile back as
+// 16-byte row chunks, adds the residual (16-byte loads) and stores 16 bytes per lane, so a store
+// instruction covers whole 128-byte row segments.  The destination row pointers (plain output,
+// or the K / V cache rows of the sample the row belongs to) are computed once per chunk.
 template <int FM, int FN>
 __device__ __forceinline__ void store_tile_epilogue(floatx16_t (&acc)[FM][FN], const EpiParams &ep,
-                                                    int rows, int N, int wrow0, int wcol0, int lane)
+                                                    int rows, int N, int wrow0, int wcol0, int lane,
+                                                    uint16_t *wlds)
 {
+    constexpr int TM = FM * 32, TN = FN * 32, PITCH = TN + 8;
     const int rl = lane & 31, g = lane >> 5;
     const uint16_t *bias = reinterpret_cast<const uint16_t *>(ep.bias);
-    const uint16_t *res = reinterpret_cast<const uint16_t *>(ep.residual);
     const int odd = lane & 1;
-    const bool routed = ep.split < N;                       // K/V columns go to the cache
-    const float inv_rps = 1.0f / (float)ep.rows_per_sample;
-    float bv[FN];
-    int pcol[FN];
-    bool col_ok[FN];
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
         const int col = wcol0 + j * 32 + rl;
-        col_ok[j] = col < N;
-        bv[j] = (bias && col_ok[j]) ? bf16_to_f32(bias[col]) : 0.f;
-        pcol[j] = col - odd;                                 // even column of the stored pair
-    }
+        const float bv = (bias && col < N) ? bf16_to_f32(bias[col]) : 0.f;
+        const int lcol = j * 32 + rl - odd;                  // even column of the stored pair
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
+        for (int i = 0; i < FM; ++i) {
 #pragma unroll
-        for (int e = 0; e < 16; e += 2) {
-            const int row = wrow0 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3) + odd;
-            const bool row_ok = row < rows;
-            uint16_t *out_row = (uint16_t *)ep.out0 + (size_t)row * ep.ld0;
-            const uint16_t *res_row = res + (size_t)row * N;
-            uint16_t *k_row = nullptr, *v_row = nullptr;
-            if (routed) {
-                // sample index: float estimate, then one exact correction step
-                int b = (int)(((float)row + 0.5f) * inv_rps);
-                int j0 = row - b * ep.rows_per_sample;
-                if (j0 < 0) { --b; j0 += ep.rows_per_sample; }
-                else if (j0 >= ep.rows_per_sample) { ++b; j0 -= ep.rows_per_sample; }
-                const size_t crow = (size_t)b * ep.cap + ep.len + j0;
-                k_row = (uint16_t *)ep.kcache + crow * ep.hd;
-                v_row = (uint16_t *)ep.vcache + crow * ep.hd;
-            }
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                float v0 = acc[i][j][e] + bv[j], v1 = acc[i][j][e + 1] + bv[j];
+            for (int e = 0; e < 16; e += 2) {
+                float v0 = acc[i][j][e] + bv, v1 = acc[i][j][e + 1] + bv;
                 if (ep.gelu) { v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); }
                 const float send = odd ? v0 : v1;
                 const float recv = __shfl_xor(send, 1);
-                float lo = odd ? recv : v0, hi = odd ? v1 : recv;
-                if (row_ok && col_ok[j]) {
-                    if (res) {
-                        const uint32_t rv = *reinterpret_cast<const uint32_t *>(res_row + pcol[j]);
-                        lo += bf16_lo(rv);
-                        hi += bf16_hi(rv);
-                    }
-                    uint16_t *dst;
-                    const int c = pcol[j] - ep.split;
-                    if (c < 0) dst = out_row + pcol[j];
-                    else if (c < ep.hd) dst = k_row + c;
-                    else dst = v_row + (c - ep.hd);
-                    *reinterpret_cast<uint32_t *>(dst) = pack_bf16x2(lo, hi);
-                }
+                const int lrow = i * 32 + 8 * (e >> 2) + 4 * g + (e & 3) + odd;
+                *reinterpret_cast<uint32_t *>(wlds + lrow * PITCH + lcol) =
+                    odd ? pack_bf16x2(recv, v1) : pack_bf16x2(v0, recv);
             }
         }
+    }
+    // the region is private to this wavefront and LDS operations of one wavefront complete in
+    // order, so no barrier is needed between the two phases
+    constexpr int CPR = TN / 8, RPI = 64 / CPR;             // chunks per row, rows per instruction
+    const uint16_t *res = reinterpret_cast<const uint16_t *>(ep.residual);
+    const bool routed = ep.split < N;                       // K/V columns go to the cache
+    const float inv_rps = 1.0f / (float)ep.rows_per_sample;
+    const int lc = (lane % CPR) * 8, col = wcol0 + lc;
+#pragma unroll
+    for (int it = 0; it < TM / RPI; ++it) {
+        const int lrow = it * RPI + lane / CPR, row = wrow0 + lrow;
+        uint4 v = *reinterpret_cast<const uint4 *>(wlds + lrow * PITCH + lc);
+        if (row >= rows || col >= N) continue;
+        if (res) {
+            const uint4 rv = *reinterpret_cast<const uint4 *>(res + (size_t)row * N + col);
+            float a[8], r[8];
+            Elem<uint16_t>::unpack(v, a);
+            Elem<uint16_t>::unpack(rv, r);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) a[t] += r[t];
+            v = Elem<uint16_t>::pack(a);
+        }
+        uint16_t *dst;
+        const int c = col - ep.split;
+        if (!routed || c < 0) {
+            dst = (uint16_t *)ep.out0 + (size_t)row * ep.ld0 + col;
+        } else {
+            // sample index: float estimate, then one exact correction step
+            int b = (int)(((float)row + 0.5f) * inv_rps);
+            int j0 = row - b * ep.rows_per_sample;
+            if (j0 < 0) { --b; j0 += ep.rows_per_sample; }
+            else if (j0 >= ep.rows_per_sample) { ++b; j0 -= ep.rows_per_sample; }
+            const size_t crow = (size_t)b * ep.cap + ep.len + j0;
+            dst = (c < ep.hd) ? (uint16_t *)ep.kcache + crow * ep.hd + c
+                              : (uint16_t *)ep.vcache + crow * ep.hd + (c - ep.hd);
+        }
+        *reinterpret_cast<uint4 *>(dst) = v;
     }
 }
 
@@ -145,7 +151,7 @@ template <int BM, int BN, int WM, int WN, int STAGES>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t *__restrict__ A,
                                                             const uint16_t *__restrict__ W, int rows,
                                                             int N, int K, int tiles_m, int tiles_n,
-                                                            EpiParams ep)
+                                                            int group_m, EpiParams ep)
 {
     constexpr int NW = WM * WN;                        // wavefronts per workgroup
     constexpr int TM = BM / WM, TN = BN / WN;
@@ -160,12 +166,13 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t 
     const int per_xcd = (gridDim.x + 7) / 8;
     int pid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (pid >= ntiles) return;
-    constexpr int GROUP_M = 8;
-    const int group = pid / (GROUP_M * tiles_n);
-    const int first_m = group * GROUP_M;
-    const int gsize = min(tiles_m - first_m, GROUP_M);
-    const int tm = first_m + (pid % (GROUP_M * tiles_n)) % gsize;
-    const int tn = (pid % (GROUP_M * tiles_n)) / gsize;
+    // consecutive tile ids run down group_m row tiles, then across the columns: the contiguous
+    // id range of one XCD is a patch of about group_m x (tiles/8/group_m) tiles
+    const int group = pid / (group_m * tiles_n);
+    const int first_m = group * group_m;
+    const int gsize = min(tiles_m - first_m, group_m);
+    const int tm = first_m + (pid % (group_m * tiles_n)) % gsize;
+    const int tn = (pid % (group_m * tiles_n)) / gsize;
     const int row0 = tm * BM, col0 = tn * BN;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -190,8 +197,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t 
         b_off[i] = (uint32_t)(((size_t)min(col0 + r, N - 1) * K + c * 8) * sizeof(uint16_t));
     }
     const int ktiles = K / BK;
-    auto issue = [&](int kt, int stage) {               // DMA of k-tile kt (clamped) into `stage`
-        const int koff = min(kt, ktiles - 1) * BK;
+    auto issue = [&](int kt, int stage) {               // DMA of k-tile kt into `stage`
+        const int koff = kt * BK;
         const uint32_t sbase = lds_base + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
         for (int i = 0; i < NGA; ++i) dma_b128(A + koff, a_off[i], sbase + i * (NW * 1024));
@@ -220,16 +227,22 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t 
     };
 
     // prologue: STAGES-1 tiles in flight, the first one landed
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s) issue(s, s);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG * (STAGES - 2)) : "memory");
+    issue(0, 0);
+    if (STAGES == 3 && ktiles > 1) {
+        issue(1, 1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG) : "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     __syncthreads();
 
+    static_assert(STAGES == 2 || STAGES == 3, "wait counts below are written for 2 or 3 stages");
     int stage = 0;                                       // stage holding k-tile kt
     for (int kt = 0; kt < ktiles; ++kt) {
         int wstage = stage + STAGES - 1;
         if (wstage >= STAGES) wstage -= STAGES;
-        issue(kt + STAGES - 1, wstage);                  // that stage was read in iteration kt-1
+        const bool ahead = kt + STAGES - 1 < ktiles;     // uniform
+        if (ahead) issue(kt + STAGES - 1, wstage);       // that stage was read in iteration kt-1
         __builtin_amdgcn_sched_barrier(0);
         const uint16_t *cur = lds + stage * (STAGE_BYTES / 2);
         bf16x8_t af[2][FM], bfr[2][FN];
@@ -246,13 +259,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t 
                                                                         acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // k-tile kt+1 has landed once only the newest STAGES-2 tiles' loads are outstanding
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG * (STAGES - 2)) : "memory");
+        // k-tile kt+1 has landed once only the requests of the tiles after it are outstanding
+        if (STAGES == 3 && ahead) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         stage = stage + 1 == STAGES ? 0 : stage + 1;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // drain the clamped tail requests
-    store_tile_epilogue<FM, FN>(acc, ep, rows, N, row0 + wm * TM, col0 + wn * TN, lane);
+    // every request has landed and every wavefront is past its last operand read (barrier above):
+    // the stage buffers are free for the epilogue's staging
+    uint16_t *wlds = reinterpret_cast<uint16_t *>(lds_raw) + wave * (TM * (TN + 8));
+    store_tile_epilogue<FM, FN>(acc, ep, rows, N, row0 + wm * TM, col0 + wn * TN, lane, wlds);
 }
 
 template <int BM, int BN, int WM, int WN, int STAGES>
@@ -262,7 +278,9 @@ static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, 
     const int tiles_m = (rows + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int ntiles = tiles_m * tiles_n;
     const int grid = (ntiles + 7) / 8 * 8;
-    const size_t lds = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
+    const size_t lds_stages = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
+    const size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
+    const size_t lds = lds_stages > lds_epi ? lds_stages : lds_epi;
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, STAGES>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -270,8 +288,15 @@ static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, 
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
+    // patch height that minimises what one XCD has to pull through its own L2: a patch of g x c
+    // tiles reads g row strips (BM x K) and c column strips (BN x K), with g * c = tiles / 8
+    int group_m = (int)lround(sqrt((double)ntiles * BN / (8.0 * BM)));
+#ifdef FVAR_GROUP_M_OVERRIDE
+    if (FVAR_GROUP_M_OVERRIDE > 0) group_m = FVAR_GROUP_M_OVERRIDE;      // tuning harness only
+#endif
+    group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, st, (const uint16_t *)A,
-                       (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, ep);
+                       (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, group_m, ep);
 }
 
 // ------------------------------------------------------------------------------ fp32 FMA
