@@ -21,6 +21,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 WORKLOAD = "var_d30_512_bf16"
+# HBM-side bytes per GEMM launch (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size;
+# profiles/pruned_chain_var_d30_512_hbm_counters.txt).  Set to None whenever gemm.hip changes
+# until the counters are taken again.
+GEMM_TRAFFIC_BYTES = 172.4e6
 
 
 class Chain:
@@ -234,7 +238,7 @@ def main():
     achieved = g_flop / (g_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (qkv, o, fc1, fc2 launches)",
                 "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES,
                 "avg_launch_us": round(g_ms * 1e3 / g_launch, 2),
                 "flop_per_launch": g_flop / g_launch,
                 "share_of_kernel_time": round(g_ms / total_ms, 3)}
