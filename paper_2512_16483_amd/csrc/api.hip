@@ -13,6 +13,8 @@
 
 using fvar::DType;
 
+thread_local fvar::LaunchProbe *fvar::g_probe = nullptr;
+
 struct fvar_ctx {
     fvar_config cfg;
     std::vector<int32_t> scale_hw;
@@ -53,15 +55,17 @@ hipEvent_t get_event(fvar_ctx *c)
     return e;
 }
 
-// Runs `launch` bracketed by an event pair when profiling is on.
+// Runs `launch` (one kernel) with its start/stop recorded in an event pair when profiling is on.
 template <typename F>
 void timed(fvar_ctx *c, hipStream_t st, const char *label, F &&launch)
 {
     if (!c->profiling) { launch(); return; }
     fvar_ctx::Rec r{label, get_event(c), get_event(c)};
-    (void)hipEventRecord(r.a, st);
+    fvar::LaunchProbe probe{r.a, r.b};
+    fvar::g_probe = &probe;                   // the (single) kernel launch inside records into it
     launch();
-    (void)hipEventRecord(r.b, st);
+    fvar::g_probe = nullptr;
+    (void)st;
     c->recs.push_back(r);
 }
 

@@ -311,7 +311,7 @@ static void launch_attn_bf16(const void *q, const void *K, const void *V, int B,
         attr_set = true;
     }
     dim3 grid((n + BQ - 1) / BQ, H, B), block(256);
-    hipLaunchKernelGGL(kern, grid, block, lds, st, (const uint16_t *)q, (const uint16_t *)K,
+    launch(kern, grid, block, lds, st, (const uint16_t *)q, (const uint16_t *)K,
                        (const uint16_t *)V, n, L, cap, H, scale * 1.4426950408889634f,
                        (uint16_t *)o);
 }
@@ -409,10 +409,10 @@ void launch_attention(DType dt, const void *q, const void *K, const void *V, int
     } else {
         dim3 grid((n + 31) / 32, H, B), block(256);
         if (Dh == 64)
-            hipLaunchKernelGGL(attn_f32_kernel<64>, grid, block, 0, st, (const float *)q,
+            launch(attn_f32_kernel<64>, grid, block, 0, st, (const float *)q,
                                (const float *)K, (const float *)V, n, L, cap, H, scale, (float *)o);
         else
-            hipLaunchKernelGGL(attn_f32_kernel<128>, grid, block, 0, st, (const float *)q,
+            launch(attn_f32_kernel<128>, grid, block, 0, st, (const float *)q,
                                (const float *)K, (const float *)V, n, L, cap, H, scale, (float *)o);
     }
 }

@@ -1,6 +1,7 @@
 // Shared device helpers and the host-side launcher interface of the fvar kernels (gfx950 only).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #define FVAR_WAVE 64
@@ -80,6 +81,21 @@ __device__ __forceinline__ double wave_sum(double v)
 namespace fvar {
 
 enum class DType : int { F32 = 0, BF16 = 1 };
+
+// Kernel launch used by every launcher.  While per-kernel timing is switched on, the API layer
+// points g_probe at an event pair and the launch records the kernel's own start and stop in it
+// (hipExtLaunchKernel), which excludes the dispatch gap between consecutive kernels.
+struct LaunchProbe { hipEvent_t start, stop; };
+extern thread_local LaunchProbe *g_probe;
+template <typename F, typename... Args>
+inline void launch(F kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args)
+{
+    if (g_probe)
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, g_probe->start, g_probe->stop, 0,
+                              args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+}
 
 // scores[b,i] = fl32(sum_j x[b,i,j]^2), fp64 accumulation
 void launch_scores(DType dt, const void *x, int rows, int d, float *scores, hipStream_t st);

@@ -15,15 +15,15 @@
 namespace fvar {
 
 // ------------------------------------------------------------------ kept rows: scatter
+// Workgroup `blk` of the scatter part: four rows, one per wavefront.
 template <typename T>
-__global__ __launch_bounds__(256) void scatter_rows_kernel(const T *__restrict__ y_keep,
-                                                           const int32_t *__restrict__ idx_keep,
-                                                           int M, int k, int total_rows, int d,
-                                                           T *__restrict__ y)
+__device__ __forceinline__ void scatter_rows(int blk, const T *__restrict__ y_keep,
+                                             const int32_t *__restrict__ idx_keep, int M, int k,
+                                             int total_rows, int d, T *__restrict__ y)
 {
     constexpr int E = Elem<T>::kPerChunk;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + wave;
+    const int row = blk * 4 + wave;
     if (row >= total_rows) return;
     const int b = row / k;
     const int dst_row = idx_keep ? idx_keep[row] : row - b * k;
@@ -37,20 +37,31 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const T *__restrict__
 constexpr int kFillCols = 128;     // column slab per workgroup
 constexpr int kFillRows = 128;     // pruned rows per workgroup iteration (4 waves x 32)
 
-__global__ __launch_bounds__(256) void fill_bf16_kernel(const int32_t *__restrict__ idx_drop, int M,
-                                                        int nd, int r, int d,
+// One launch does both parts: workgroups [0, fill_blocks) restore pruned rows (slab, row share and
+// sample decoded from the block id), the workgroups after them copy kept rows.
+__global__ __launch_bounds__(256) void fill_bf16_kernel(const uint16_t *__restrict__ y_keep,
+                                                        const int32_t *__restrict__ idx_keep,
+                                                        const int32_t *__restrict__ idx_drop, int M,
+                                                        int k, int B, int r, int d,
                                                         const uint16_t *__restrict__ w_c,
                                                         const uint16_t *__restrict__ g_c,
-                                                        uint16_t *__restrict__ y, int row_split)
+                                                        uint16_t *__restrict__ y, int slabs,
+                                                        int row_split, int fill_blocks)
 {
+    if ((int)blockIdx.x >= fill_blocks) {
+        scatter_rows<uint16_t>(blockIdx.x - fill_blocks, y_keep, idx_keep, M, k, B * k, d, y);
+        return;
+    }
+    const int nd = M - k;
+    const int slab = blockIdx.x % slabs, share = (blockIdx.x / slabs) % row_split;
+    const int b = blockIdx.x / (slabs * row_split);
     extern __shared__ uint4 lds_raw[];
     uint16_t *gt = reinterpret_cast<uint16_t *>(lds_raw);     // [kFillCols][pitch]
     const int rp = (r + 15) & ~15;                            // k extent padded to the MFMA step
     const int pitch = rp + 8;                                 // odd number of 16 B chunks per row
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rl = lane & 31, g = lane >> 5;
-    const int b = blockIdx.z;
-    const int col0 = blockIdx.x * kFillCols;
+    const int col0 = slab * kFillCols;
     const uint16_t *G = g_c + (size_t)b * r * d;
     const uint16_t *W = w_c + (size_t)b * M * r;
     const int32_t *drop = idx_drop + (size_t)b * nd;
@@ -88,7 +99,7 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(const int32_t *__restric
 
     const int ksteps = rp / 16;
     const int iters = (nd + kFillRows - 1) / kFillRows;
-    for (int it = blockIdx.y; it < iters; it += row_split) {
+    for (int it = share; it < iters; it += row_split) {
         const int j0 = it * kFillRows + wave * 32;
         if (j0 >= nd) continue;                                // wave-uniform
         // A operand: lane (row rl, half g) holds w_c[row][16s + 8g .. +8)
@@ -132,14 +143,21 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(const int32_t *__restric
 }
 
 // ------------------------------------------------------------------ pruned rows, fp32 FMA
-__global__ __launch_bounds__(256) void fill_f32_kernel(const int32_t *__restrict__ idx_drop, int M,
-                                                       int nd, int r, int d,
+__global__ __launch_bounds__(256) void fill_f32_kernel(const float *__restrict__ y_keep,
+                                                       const int32_t *__restrict__ idx_keep,
+                                                       const int32_t *__restrict__ idx_drop, int M,
+                                                       int k, int B, int r, int d,
                                                        const float *__restrict__ w_c,
                                                        const float *__restrict__ g_c,
-                                                       float *__restrict__ y)
+                                                       float *__restrict__ y, int fill_blocks)
 {
     __shared__ float wrow[256];
-    const int b = blockIdx.y, j = blockIdx.x;
+    if ((int)blockIdx.x >= fill_blocks) {
+        scatter_rows<float>(blockIdx.x - fill_blocks, y_keep, idx_keep, M, k, B * k, d, y);
+        return;
+    }
+    const int nd = M - k;
+    const int b = blockIdx.x / nd, j = blockIdx.x % nd;
     const int i = idx_drop[(size_t)b * nd + j];
     const float *W = w_c + ((size_t)b * M + i) * r;
     const float *G = g_c + (size_t)b * r * d;
@@ -163,36 +181,29 @@ void launch_fill(DType dt, const void *y_keep, const int32_t *idx_keep, const in
                  hipStream_t st)
 {
     const int nd = M - k;
-    if (k > 0) {
-        const int total = B * k;
-        dim3 grid((total + 3) / 4), block(256);
-        if (dt == DType::BF16)
-            hipLaunchKernelGGL(scatter_rows_kernel<uint16_t>, grid, block, 0, st,
-                               (const uint16_t *)y_keep, idx_keep, M, k, total, d, (uint16_t *)y);
-        else
-            hipLaunchKernelGGL(scatter_rows_kernel<float>, grid, block, 0, st, (const float *)y_keep,
-                               idx_keep, M, k, total, d, (float *)y);
-    }
-    if (nd <= 0) return;
+    const int scatter_blocks = (B * k + 3) / 4;
     if (dt == DType::BF16) {
         const int slabs = (d + kFillCols - 1) / kFillCols;
         const int iters = (nd + kFillRows - 1) / kFillRows;
         // enough workgroups to cover the chip a few times, but keep the slab staging amortised
-        int row_split = (1024 + slabs * B - 1) / (slabs * B);
+        int row_split = nd > 0 ? (1024 + slabs * B - 1) / (slabs * B) : 0;
         if (row_split > iters) row_split = iters;
-        if (row_split < 1) row_split = 1;
+        const int fill_blocks = slabs * row_split * B;
         const int rp = (r + 15) & ~15;
-        const size_t lds = (size_t)kFillCols * (rp + 8) * sizeof(uint16_t);
+        const size_t lds = nd > 0 ? (size_t)kFillCols * (rp + 8) * sizeof(uint16_t) : 0;
         if (lds > 48 * 1024)
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(fill_bf16_kernel),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        dim3 grid(slabs, row_split, B), block(256);
-        hipLaunchKernelGGL(fill_bf16_kernel, grid, block, lds, st, idx_drop, M, nd, r, d,
-                           (const uint16_t *)w_c, (const uint16_t *)g_c, (uint16_t *)y, row_split);
+        if (fill_blocks + scatter_blocks == 0) return;
+        launch(fill_bf16_kernel, dim3(fill_blocks + scatter_blocks), dim3(256), lds, st,
+               (const uint16_t *)y_keep, idx_keep, idx_drop, M, k, B, r, d, (const uint16_t *)w_c,
+               (const uint16_t *)g_c, (uint16_t *)y, slabs, row_split, fill_blocks);
     } else {
-        dim3 grid(nd, B), block(256);
-        hipLaunchKernelGGL(fill_f32_kernel, grid, block, 0, st, idx_drop, M, nd, r, d,
-                           (const float *)w_c, (const float *)g_c, (float *)y);
+        const int fill_blocks = nd * B;
+        if (fill_blocks + scatter_blocks == 0) return;
+        launch(fill_f32_kernel, dim3(fill_blocks + scatter_blocks), dim3(256), 0, st,
+               (const float *)y_keep, idx_keep, idx_drop, M, k, B, r, d, (const float *)w_c,
+               (const float *)g_c, (float *)y, fill_blocks);
     }
 }
 

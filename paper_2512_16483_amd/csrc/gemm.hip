@@ -295,7 +295,7 @@ static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, 
     if (FVAR_GROUP_M_OVERRIDE > 0) group_m = FVAR_GROUP_M_OVERRIDE;      // tuning harness only
 #endif
     group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, st, (const uint16_t *)A,
+    launch(kern, dim3(grid), dim3(64 * WM * WN), lds, st, (const uint16_t *)A,
                        (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, group_m, ep);
 }
 
@@ -387,7 +387,7 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
         }
     } else {
         dim3 grid((N + 63) / 64, (rows + 63) / 64), block(256);
-        hipLaunchKernelGGL(gemm_f32_kernel, grid, block, 0, st, (const float *)A, (const float *)W,
+        launch(gemm_f32_kernel, grid, block, 0, st, (const float *)A, (const float *)W,
                            rows, N, K, ep);
     }
 }

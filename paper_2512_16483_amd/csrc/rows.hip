@@ -99,7 +99,7 @@ static void launch_gather_ln_t(const void *x, const int32_t *idx, int B, int M, 
     const int ch = (nchunk + 63) / 64;
     dim3 grid((total + 3) / 4), block(256);
 #define FVAR_GLN(CH)                                                                             \
-    hipLaunchKernelGGL((gather_ln_kernel<T, CH>), grid, block, 0, st, (const T *)x, idx, M, n,    \
+    launch((gather_ln_kernel<T, CH>), grid, block, 0, st, (const T *)x, idx, M, n,    \
                        total, d, (const T *)gamma, (const T *)beta, eps, (T *)copy_out,           \
                        (T *)ln_out)
     if (ch <= 2) FVAR_GLN(2);

@@ -57,10 +57,10 @@ void launch_scores(DType dt, const void *x, int rows, int d, float *scores, hipS
 {
     dim3 grid((rows + 3) / 4), block(256);
     if (dt == DType::BF16)
-        hipLaunchKernelGGL(scores_kernel<uint16_t>, grid, block, 0, st, (const uint16_t *)x, rows, d,
+        launch(scores_kernel<uint16_t>, grid, block, 0, st, (const uint16_t *)x, rows, d,
                            scores);
     else
-        hipLaunchKernelGGL(scores_kernel<float>, grid, block, 0, st, (const float *)x, rows, d,
+        launch(scores_kernel<float>, grid, block, 0, st, (const float *)x, rows, d,
                            scores);
 }
 
@@ -188,10 +188,10 @@ void launch_select(const float *scores, int B, int M, int k, int32_t *idx_keep, 
 {
     dim3 grid(B), block(kSelThreads);
     if (M <= 12288) {
-        hipLaunchKernelGGL(select_kernel<true>, grid, block, (size_t)M * sizeof(uint32_t), st, scores,
+        launch(select_kernel<true>, grid, block, (size_t)M * sizeof(uint32_t), st, scores,
                            M, k, idx_keep, idx_drop);
     } else {
-        hipLaunchKernelGGL(select_kernel<false>, grid, block, 0, st, scores, M, k, idx_keep,
+        launch(select_kernel<false>, grid, block, 0, st, scores, M, k, idx_keep,
                            idx_drop);
     }
 }
