@@ -36,6 +36,7 @@ __device__ __forceinline__ void scatter_rows(int blk, const T *__restrict__ y_ke
 // ------------------------------------------------------------------ pruned rows, bf16 MFMA
 constexpr int kFillCols = 128;     // column slab per workgroup
 constexpr int kFillRows = 128;     // pruned rows per workgroup iteration (4 waves x 32)
+constexpr int kFillPitch = kFillCols + 8;   // row pitch (elements) of the output staging
 
 // One launch does both parts: workgroups [0, fill_blocks) restore pruned rows (slab, row share and
 // sample decoded from the block id), the workgroups after them copy kept rows.
@@ -61,6 +62,7 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(const uint16_t *__restri
     const int pitch = rp + 8;                                 // odd number of 16 B chunks per row
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rl = lane & 31, g = lane >> 5;
+    uint16_t *wl = gt + (size_t)kFillCols * pitch + wave * (32 * kFillPitch);   // output staging
     const int col0 = slab * kFillCols;
     const uint16_t *G = g_c + (size_t)b * r * d;
     const uint16_t *W = w_c + (size_t)b * M * r;
@@ -112,16 +114,13 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(const uint16_t *__restri
             afrag[s] = (s < ksteps && t < r) ? *reinterpret_cast<const uint4 *>(wrow + t)
                                              : make_uint4(0, 0, 0, 0);
         }
-        // destination rows of this lane's accumulator entries
-        int32_t drow[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int rr = j0 + 8 * (i >> 2) + 4 * g + (i & 3);
-            drow[i] = rr < nd ? drop[rr] : -1;
-        }
+        // The four 32x32 accumulator tiles of this row block are packed to bf16 (adjacent lanes
+        // swap one value per row pair so that a lane owns two neighbouring columns) and parked
+        // row-major in this wavefront's private LDS region; they leave as 16-byte row chunks, so
+        // a store instruction writes whole 256-byte row segments.
+        const int odd = lane & 1;
 #pragma unroll 1
         for (int cb = 0; cb < kFillCols / 32; ++cb) {
-            const int col = col0 + cb * 32 + rl;
             floatx16_t acc = {0};
             const uint16_t *bsrc = gt + (size_t)(cb * 32 + rl) * pitch + 8 * g;
 #pragma unroll
@@ -133,11 +132,24 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(const uint16_t *__restri
                         0, 0, 0);
                 }
             }
-            if (col < d) {
+            const int lcol = cb * 32 + rl - odd;
 #pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    if (drow[i] >= 0) Y[(size_t)drow[i] * d + col] = f32_to_bf16(acc[i]);
+            for (int e = 0; e < 16; e += 2) {
+                const float v0 = acc[e], v1 = acc[e + 1];
+                const float recv = __shfl_xor(odd ? v0 : v1, 1);
+                const int lrow = 8 * (e >> 2) + 4 * g + (e & 3) + odd;
+                *reinterpret_cast<uint32_t *>(wl + lrow * kFillPitch + lcol) =
+                    odd ? pack_bf16x2(recv, v1) : pack_bf16x2(v0, recv);
             }
+        }
+        // same wavefront wrote and reads the region: LDS operations of a wavefront stay in order
+        const int c = (lane & 15) * 8;
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int lrow = it * 4 + (lane >> 4), rr = j0 + lrow;
+            const uint4 v = *reinterpret_cast<const uint4 *>(wl + lrow * kFillPitch + c);
+            if (rr < nd && col0 + c < d)
+                *reinterpret_cast<uint4 *>(Y + (size_t)drop[rr] * d + col0 + c) = v;
         }
     }
 }
@@ -190,7 +202,7 @@ void launch_fill(DType dt, const void *y_keep, const int32_t *idx_keep, const in
         if (row_split > iters) row_split = iters;
         const int fill_blocks = slabs * row_split * B;
         const int rp = (r + 15) & ~15;
-        const size_t lds = nd > 0 ? (size_t)kFillCols * (rp + 8) * sizeof(uint16_t) : 0;
+        const size_t lds = nd > 0 ? ((size_t)kFillCols * (rp + 8) + 4 * 32 * kFillPitch) * sizeof(uint16_t) : 0;
         if (lds > 48 * 1024)
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(fill_bf16_kernel),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
