@@ -147,13 +147,15 @@ __device__ __forceinline__ void dma_b128(const void *base, uint32_t byte_off, ui
                  :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t *__restrict__ A,
-                                                            const uint16_t *__restrict__ W, int rows,
-                                                            int N, int K, int tiles_m, int tiles_n,
-                                                            int group_m, EpiParams ep)
+// KS > 1 splits every k-tile between KS groups of WM x WN wavefronts (group ks takes the 16-wide
+// k-steps ks, ks+KS, ...); the groups' partial accumulators are summed through LDS before the
+// epilogue.  This doubles the wavefronts per CU for problems that give a CU only one small tile.
+template <int BM, int BN, int WM, int WN, int STAGES, int KS>
+__global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
+    const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, int rows, int N, int K,
+    int tiles_m, int tiles_n, int group_m, EpiParams ep)
 {
-    constexpr int NW = WM * WN;                        // wavefronts per workgroup
+    constexpr int NW = WM * WN * KS;                   // wavefronts per workgroup
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int FM = TM / 32, FN = TN / 32;
     constexpr int NGA = BM / 8 / NW, NGB = BN / 8 / NW; // 1 KiB groups (8 rows) per wavefront
@@ -178,7 +180,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rl = lane & 31, g = lane >> 5;
-    const int wm = wave / WN, wn = wave % WN;
+    const int ks = wave / (WM * WN), wsub = wave % (WM * WN);
+    const int wm = wsub / WN, wn = wsub % WN;
 
     // ---- DMA assignment: wavefront w owns the 8-row groups w, w+NW, ... of each tile; lane l of a
     // group fills physical chunk l%8 of row 8*group + l/8, i.e. it fetches the logical chunk that
@@ -245,17 +248,19 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t 
         if (ahead) issue(kt + STAGES - 1, wstage);       // that stage was read in iteration kt-1
         __builtin_amdgcn_sched_barrier(0);
         const uint16_t *cur = lds + stage * (STAGE_BYTES / 2);
+        constexpr int STEPS = BK / 16 / KS;               // k-steps of this wavefront per k-tile
         bf16x8_t af[2][FM], bfr[2][FN];
-        load_frags(cur, 0, af[0], bfr[0]);
+        load_frags(cur, ks, af[0], bfr[0]);
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            if (kk + 1 < BK / 16) load_frags(cur, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+        for (int q = 0; q < STEPS; ++q) {
+            if (q + 1 < STEPS)
+                load_frags(cur, (q + 1) * KS + ks, af[(q + 1) & 1], bfr[(q + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j],
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[q & 1][i], bfr[q & 1][j],
                                                                         acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -266,12 +271,34 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_bf16_kernel(const uint16_t 
         stage = stage + 1 == STAGES ? 0 : stage + 1;
     }
     // every request has landed and every wavefront is past its last operand read (barrier above):
-    // the stage buffers are free for the epilogue's staging
-    uint16_t *wlds = reinterpret_cast<uint16_t *>(lds_raw) + wave * (TM * (TN + 8));
+    // the stage buffers are free for the k-split reduction and the epilogue's staging
+    constexpr int RED_FLOATS = KS > 1 ? WM * WN * FM * FN * 16 * 64 : 0;
+    if (KS > 1) {
+        // partial accumulators in lane-major order: entry (tile, e) of lane l at (tile*16+e)*64 + l
+        float *red = reinterpret_cast<float *>(lds_raw) + wsub * (FM * FN * 16 * 64) + lane;
+        if (ks != 0) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) red[((i * FN + j) * 16 + e) * 64] = acc[i][j][e];
+        }
+        __syncthreads();
+        if (ks != 0) return;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] += red[((i * FN + j) * 16 + e) * 64];
+    }
+    uint16_t *wlds = reinterpret_cast<uint16_t *>(reinterpret_cast<float *>(lds_raw) + RED_FLOATS) +
+                     wsub * (TM * (TN + 8));
     store_tile_epilogue<FM, FN>(acc, ep, rows, N, row0 + wm * TM, col0 + wn * TN, lane, wlds);
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES>
+template <int BM, int BN, int WM, int WN, int STAGES, int KS = 1>
 static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, int K,
                                  const EpiParams &ep, hipStream_t st)
 {
@@ -279,9 +306,10 @@ static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, 
     const int ntiles = tiles_m * tiles_n;
     const int grid = (ntiles + 7) / 8 * 8;
     const size_t lds_stages = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
-    const size_t lds_epi = (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
+    const size_t lds_red = KS > 1 ? (size_t)BM * BN * sizeof(float) : 0;
+    const size_t lds_epi = lds_red + (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
     const size_t lds = lds_stages > lds_epi ? lds_stages : lds_epi;
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, STAGES>;
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, STAGES, KS>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -295,7 +323,7 @@ static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, 
     if (FVAR_GROUP_M_OVERRIDE > 0) group_m = FVAR_GROUP_M_OVERRIDE;      // tuning harness only
 #endif
     group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
-    launch(kern, dim3(grid), dim3(64 * WM * WN), lds, st, (const uint16_t *)A,
+    launch(kern, dim3(grid), dim3(64 * WM * WN * KS), lds, st, (const uint16_t *)A,
                        (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, group_m, ep);
 }
 
@@ -368,14 +396,14 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
         // x tile area / sustained rate of the configuration (TFLOP/s measured on large problems)
         struct Cand { int bm, bn; double rate; };
         const Cand cands[4] = {{256, 256, 1155.0}, {256, 128, 1045.0}, {128, 256, 1041.0},
-                               {128, 128, 935.0}};
+                               {128, 128, 1000.0}};
         int best = 0;
         double best_cost = 1e300;
         for (int i = 0; i < 4; ++i) {
             const long tiles = (long)((rows + cands[i].bm - 1) / cands[i].bm) *
                                ((N + cands[i].bn - 1) / cands[i].bn);
             double rate = cands[i].rate;
-            if (i == 3 && tiles > 256) rate = 600.0;       // small tiles pay per round
+            if (i == 3 && tiles > 256) rate = 650.0;       // small tiles pay per round
             const double cost = (double)((tiles + 255) / 256) * cands[i].bm * cands[i].bn / rate;
             if (cost < best_cost) { best_cost = cost; best = i; }
         }
@@ -383,7 +411,7 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
         case 0: launch_gemm_bf16_cfg<256, 256, 2, 4, 2>(A, W, rows, N, K, ep, st); break;
         case 1: launch_gemm_bf16_cfg<256, 128, 4, 2, 3>(A, W, rows, N, K, ep, st); break;
         case 2: launch_gemm_bf16_cfg<128, 256, 2, 4, 3>(A, W, rows, N, K, ep, st); break;
-        default: launch_gemm_bf16_cfg<128, 128, 2, 2, 3>(A, W, rows, N, K, ep, st); break;
+        default: launch_gemm_bf16_cfg<128, 128, 2, 2, 3, 2>(A, W, rows, N, K, ep, st); break;
         }
     } else {
         dim3 grid((N + 63) / 64, (rows + 63) / 64), block(256);
