@@ -110,7 +110,7 @@ def kernel_work(W, side):
     out["score"] = ("byte", B * M * (d * es + 4.0))
     out["select"] = ("byte", B * M * 8.0)
     out["gather_ln1"] = ("byte", B * k * (3.0 * d * es + 4))
-    out["ln2"] = ("byte", B * k * 2.0 * d * es)
+    out["ln2"] = ("byte", B * k * d * (4.0 + es))       # reads the fp32 residual stream
     out["fill"] = ("byte", B * (M * d * es + k * d * es + (M - k) * r * es + r * d * es))
     return out
 

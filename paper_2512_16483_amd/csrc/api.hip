@@ -93,7 +93,7 @@ BlockWs carve(const fvar_ctx *c, void *ws, int B, int rows)
     w.u = take(R * d * es);
     w.q = take(R * d * es);
     w.att = take(R * d * es);
-    w.h1 = take(R * d * es);
+    w.h1 = take(R * d * sizeof(float));       // intermediate residual stream, always fp32
     w.hid = take(R * F * es);
     w.total = off;
     return w;
@@ -152,11 +152,15 @@ fvar_status block_forward(fvar_ctx *c, hipStream_t st, const fvar_block_weights 
     timed(c, st, "gemm_o", [&] {
         fvar::GemmEpilogue e;
         e.bias = w->b_o; e.residual = resid; e.out0 = s.h1; e.ld0 = d; e.split = d;
+        e.out_f32 = 1;
         fvar::launch_gemm(dt, s.att, w->w_o, R, d, d, e, st);
     });
     timed(c, st, "ln2", [&] {
-        fvar::launch_gather_ln(dt, s.h1, nullptr, 1, R, R, d, w->ln2_g, w->ln2_b, c->eps, nullptr, s.u,
-                               st);
+        if (dt == DType::BF16)
+            fvar::launch_ln_f32_to_bf16((const float *)s.h1, R, d, w->ln2_g, w->ln2_b, c->eps, s.u, st);
+        else
+            fvar::launch_gather_ln(dt, s.h1, nullptr, 1, R, R, d, w->ln2_g, w->ln2_b, c->eps, nullptr,
+                                   s.u, st);
     });
     timed(c, st, "gemm_fc1", [&] {
         fvar::GemmEpilogue e;
@@ -165,7 +169,7 @@ fvar_status block_forward(fvar_ctx *c, hipStream_t st, const fvar_block_weights 
     });
     timed(c, st, "gemm_fc2", [&] {
         fvar::GemmEpilogue e;
-        e.bias = w->b_fc2; e.residual = s.h1; e.out0 = y; e.ld0 = d; e.split = d;
+        e.bias = w->b_fc2; e.residual = s.h1; e.res_f32 = 1; e.out0 = y; e.ld0 = d; e.split = d;
         fvar::launch_gemm(dt, s.hid, w->w_fc2, R, d, F, e, st);
     });
     return launch_status(c, who);

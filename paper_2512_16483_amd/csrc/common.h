@@ -107,6 +107,9 @@ void launch_select(const float *scores, int B, int M, int k, int32_t *idx_keep, 
 void launch_gather_ln(DType dt, const void *x, const int32_t *idx, int B, int M, int n, int d,
                       const void *gamma, const void *beta, float eps, void *copy_out, void *ln_out,
                       hipStream_t st);
+// LayerNorm of fp32 rows h:[rows,d] into bf16 rows (gamma, beta bf16 or null)
+void launch_ln_f32_to_bf16(const float *h, int rows, int d, const void *gamma, const void *beta,
+                           float eps, void *ln_out, hipStream_t st);
 
 // C = epilogue(A[rows,K] * W[N,K]^T + bias)
 struct GemmEpilogue {
@@ -123,6 +126,10 @@ struct GemmEpilogue {
     int split = 0;                     // == N when there is no K/V routing
     void *kcache = nullptr, *vcache = nullptr;
     int hd = 0, cap = 0, len = 0, rows_per_sample = 1;
+    // bf16 path only: out0 receives fp32 (no routing, no GELU) / the residual operand is fp32.
+    // Used for the intermediate residual stream h = x + attention projection, which stays in
+    // fp32 between the two halves of the block so that it is not rounded twice.
+    int out_f32 = 0, res_f32 = 0;
 };
 void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
                  const GemmEpilogue &ep, hipStream_t st);

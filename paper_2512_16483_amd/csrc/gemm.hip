@@ -31,6 +31,8 @@ struct EpiParams {
     void *kcache, *vcache;
     int hd, cap, len, rows_per_sample;
     int N;
+    int out_f32;   // bf16 kernel: write fp32 instead of bf16 (the intermediate residual stream)
+    int res_f32;   // bf16 kernel: the residual operand is fp32
 };
 
 __device__ __forceinline__ float gelu_tanh(float v)
@@ -68,7 +70,7 @@ __device__ __forceinline__ int lds_off(int row, int chunk)      // in bf16 eleme
 // 16-byte row chunks, adds the residual (16-byte loads) and stores 16 bytes per lane, so a store
 // instruction covers whole 128-byte row segments.  The destination row pointers (plain output,
 // or the K / V cache rows of the sample the row belongs to) are computed once per chunk.
-template <int FM, int FN>
+template <int FM, int FN, bool F32_STAGED>
 __device__ __forceinline__ void store_tile_epilogue(floatx16_t (&acc)[FM][FN], const EpiParams &ep,
                                                     int rows, int N, int wrow0, int wcol0, int lane,
                                                     uint16_t *wlds)
@@ -76,6 +78,60 @@ __device__ __forceinline__ void store_tile_epilogue(floatx16_t (&acc)[FM][FN], c
     constexpr int TM = FM * 32, TN = FN * 32, PITCH = TN + 8;
     const int rl = lane & 31, g = lane >> 5;
     const uint16_t *bias = reinterpret_cast<const uint16_t *>(ep.bias);
+    if (ep.out_f32) {
+        // fp32 output (never routed, never GELU-ed; the residual operand is bf16)
+        const uint16_t *res = reinterpret_cast<const uint16_t *>(ep.residual);
+        float *out = reinterpret_cast<float *>(ep.out0);
+        if constexpr (F32_STAGED) {
+            // same two-phase scheme with an fp32 staging tile: 16-byte (4 float) row chunks out
+            constexpr int P32 = TN + 4;
+            float *w32 = reinterpret_cast<float *>(wlds);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = wcol0 + j * 32 + rl;
+                const float bv = (bias && col < N) ? bf16_to_f32(bias[col]) : 0.f;
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        w32[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * P32 + j * 32 + rl] =
+                            acc[i][j][e] + bv;
+            }
+            constexpr int CPR = TN / 4, RPI = 64 / CPR;
+            const int lc = (lane % CPR) * 4, col = wcol0 + lc;
+#pragma unroll
+            for (int it = 0; it < TM / RPI; ++it) {
+                const int lrow = it * RPI + lane / CPR, row = wrow0 + lrow;
+                float4 v = *reinterpret_cast<const float4 *>(w32 + lrow * P32 + lc);
+                if (row >= rows || col >= N) continue;
+                if (res) {
+                    const uint2 rv = *reinterpret_cast<const uint2 *>(res + (size_t)row * N + col);
+                    v.x += bf16_lo(rv.x); v.y += bf16_hi(rv.x); v.z += bf16_lo(rv.y); v.w += bf16_hi(rv.y);
+                }
+                *reinterpret_cast<float4 *>(out + (size_t)row * ep.ld0 + col) = v;
+            }
+        } else {
+            // staging tile too large for LDS: the 32 lanes of a half-wavefront still cover 128
+            // contiguous bytes of one row, so store the accumulators directly
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = wcol0 + j * 32 + rl;
+                if (col >= N) continue;
+                const float bv = bias ? bf16_to_f32(bias[col]) : 0.f;
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int row = wrow0 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+                        if (row >= rows) continue;
+                        float v = acc[i][j][e] + bv;
+                        if (res) v += bf16_to_f32(res[(size_t)row * N + col]);
+                        out[(size_t)row * ep.ld0 + col] = v;
+                    }
+            }
+        }
+        return;
+    }
     const int odd = lane & 1;
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
@@ -109,10 +165,15 @@ __device__ __forceinline__ void store_tile_epilogue(floatx16_t (&acc)[FM][FN], c
         uint4 v = *reinterpret_cast<const uint4 *>(wlds + lrow * PITCH + lc);
         if (row >= rows || col >= N) continue;
         if (res) {
-            const uint4 rv = *reinterpret_cast<const uint4 *>(res + (size_t)row * N + col);
             float a[8], r[8];
             Elem<uint16_t>::unpack(v, a);
-            Elem<uint16_t>::unpack(rv, r);
+            if (ep.res_f32) {
+                const float *rf = reinterpret_cast<const float *>(ep.residual) + (size_t)row * N + col;
+                Elem<float>::unpack(*reinterpret_cast<const uint4 *>(rf), r);
+                Elem<float>::unpack(*reinterpret_cast<const uint4 *>(rf + 4), r + 4);
+            } else {
+                Elem<uint16_t>::unpack(*reinterpret_cast<const uint4 *>(res + (size_t)row * N + col), r);
+            }
 #pragma unroll
             for (int t = 0; t < 8; ++t) a[t] += r[t];
             v = Elem<uint16_t>::pack(a);
@@ -145,6 +206,20 @@ __device__ __forceinline__ void dma_b128(const void *base, uint32_t byte_off, ui
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
+}
+
+// LDS needed after the main loop: k-split reduction buffer + one staging tile per wavefront
+constexpr size_t kLdsLimit = 160 * 1024;
+constexpr size_t gemm_red_bytes(int BM, int BN, int KS) { return KS > 1 ? (size_t)BM * BN * 4 : 0; }
+constexpr bool gemm_f32_staging_fits(int BM, int BN, int WM, int WN, int KS)
+{
+    return gemm_red_bytes(BM, BN, KS) + (size_t)BM * (BN / WN + 4) * WN * 4 <= kLdsLimit;
+}
+constexpr size_t gemm_epi_lds_bytes(int BM, int BN, int WM, int WN, int KS)
+{
+    return gemm_red_bytes(BM, BN, KS) +
+           (gemm_f32_staging_fits(BM, BN, WM, WN, KS) ? (size_t)BM * (BN / WN + 4) * WN * 4
+                                                      : (size_t)BM * (BN / WN + 8) * WN * 2);
 }
 
 // KS > 1 splits every k-tile between KS groups of WM x WN wavefronts (group ks takes the 16-wide
@@ -293,9 +368,14 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] += red[((i * FN + j) * 16 + e) * 64];
     }
-    uint16_t *wlds = reinterpret_cast<uint16_t *>(reinterpret_cast<float *>(lds_raw) + RED_FLOATS) +
-                     wsub * (TM * (TN + 8));
-    store_tile_epilogue<FM, FN>(acc, ep, rows, N, row0 + wm * TM, col0 + wn * TN, lane, wlds);
+    // per-wavefront staging region behind the reduction buffer: bf16 tile, or fp32 tile when the
+    // output is fp32 and it fits (epi_lds_bytes() below is what the launcher allocates)
+    constexpr bool F32_STAGED = gemm_f32_staging_fits(BM, BN, WM, WN, KS);
+    constexpr int WREGION = F32_STAGED ? TM * (TN + 4) * 4 : TM * (TN + 8) * 2;    // bytes
+    uint16_t *wlds = reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(lds_raw) + RED_FLOATS * 4 +
+                                                  wsub * WREGION);
+    store_tile_epilogue<FM, FN, F32_STAGED>(acc, ep, rows, N, row0 + wm * TM, col0 + wn * TN, lane,
+                                            wlds);
 }
 
 template <int BM, int BN, int WM, int WN, int STAGES, int KS = 1>
@@ -306,8 +386,7 @@ static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, 
     const int ntiles = tiles_m * tiles_n;
     const int grid = (ntiles + 7) / 8 * 8;
     const size_t lds_stages = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
-    const size_t lds_red = KS > 1 ? (size_t)BM * BN * sizeof(float) : 0;
-    const size_t lds_epi = lds_red + (size_t)WM * WN * (BM / WM) * (BN / WN + 8) * sizeof(uint16_t);
+    const size_t lds_epi = gemm_epi_lds_bytes(BM, BN, WM, WN, KS);
     const size_t lds = lds_stages > lds_epi ? lds_stages : lds_epi;
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, STAGES, KS>;
     static bool attr_set = false;
@@ -391,6 +470,8 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
     ep.hd = e.hd; ep.cap = e.cap; ep.len = e.len;
     ep.rows_per_sample = e.rows_per_sample > 0 ? e.rows_per_sample : 1;
     ep.N = N;
+    ep.out_f32 = e.out_f32;
+    ep.res_f32 = e.res_f32;
     if (dt == DType::BF16) {
         // cost = rounds of workgroups over the 256 CUs (one workgroup per CU at these LDS sizes)
         // x tile area / sustained rate of the configuration (TFLOP/s measured on large problems)

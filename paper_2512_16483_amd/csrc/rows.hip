@@ -89,6 +89,80 @@ __global__ __launch_bounds__(256) void gather_ln_kernel(const T *__restrict__ x,
     }
 }
 
+// LayerNorm of the fp32 intermediate residual stream into the bf16 operand of the MLP.
+// One wavefront per row; CH = 16-byte (4 float) chunks per lane.
+template <int CH>
+__global__ __launch_bounds__(256) void ln_f32_to_bf16_kernel(const float *__restrict__ h, int rows,
+                                                             int d,
+                                                             const uint16_t *__restrict__ gamma,
+                                                             const uint16_t *__restrict__ beta,
+                                                             float eps, uint16_t *__restrict__ out)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= rows) return;
+    const uint4 *src = reinterpret_cast<const uint4 *>(h + (size_t)row * d);
+    const int nchunk = d / 4;
+    float v[CH][4];
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int ci = lane + 64 * c;
+        const uint4 raw = ci < nchunk ? src[ci] : make_uint4(0, 0, 0, 0);
+        Elem<float>::unpack(raw, v[c]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum += v[c][e];
+    }
+    const float mu = wave_sum(sum) / (float)d;
+    float sq = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const bool in = lane + 64 * c < nchunk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float t = v[c][e] - mu;
+            v[c][e] = t;
+            sq += in ? t * t : 0.f;
+        }
+    }
+    const float rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
+    uint2 *dst = reinterpret_cast<uint2 *>(out + (size_t)row * d);
+    const uint2 *g2 = reinterpret_cast<const uint2 *>(gamma);
+    const uint2 *b2 = reinterpret_cast<const uint2 *>(beta);
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int ci = lane + 64 * c;
+        if (ci >= nchunk) continue;
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = v[c][e] * rstd;
+        if (gamma) {
+            const uint2 gv = g2[ci];
+            o[0] *= bf16_lo(gv.x); o[1] *= bf16_hi(gv.x); o[2] *= bf16_lo(gv.y); o[3] *= bf16_hi(gv.y);
+        }
+        if (beta) {
+            const uint2 bv = b2[ci];
+            o[0] += bf16_lo(bv.x); o[1] += bf16_hi(bv.x); o[2] += bf16_lo(bv.y); o[3] += bf16_hi(bv.y);
+        }
+        dst[ci] = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+    }
+}
+
+void launch_ln_f32_to_bf16(const float *h, int rows, int d, const void *gamma, const void *beta,
+                           float eps, void *ln_out, hipStream_t st)
+{
+    const int ch = (d / 4 + 63) / 64;
+    dim3 grid((rows + 3) / 4), block(256);
+#define FVAR_LN32(CH)                                                                          \
+    launch(ln_f32_to_bf16_kernel<CH>, grid, block, 0, st, h, rows, d, (const uint16_t *)gamma,  \
+           (const uint16_t *)beta, eps, (uint16_t *)ln_out)
+    if (ch <= 4) FVAR_LN32(4);
+    else if (ch <= 8) FVAR_LN32(8);
+    else if (ch <= 16) FVAR_LN32(16);
+    else FVAR_LN32(32);
+#undef FVAR_LN32
+}
+
 template <typename T>
 static void launch_gather_ln_t(const void *x, const int32_t *idx, int B, int M, int n, int d,
                                const void *gamma, const void *beta, float eps, void *copy_out,

@@ -38,8 +38,8 @@ def test_keep_count_and_schedule_helpers():
     assert fv.fvar_scale_prev_len(c, 10) == 2521 and fv.fvar_scale_tokens(c, 13) == -1
     r = fv.Context(hidden=128, heads=2, head_dim=64, ffn_hidden=256, scales=((3, 5), (4, 7)))
     assert fv.fvar_scale_tokens(r, 1) == 28 and fv.fvar_scale_prev_len(r, 1) == 15
-    # workspace: five [rows,d] buffers and one [rows,F] buffer, each rounded up to 256 bytes
-    assert fv.fvar_block_workspace_bytes(r, 2, 10) == 5 * 5120 + 10240
+    # workspace: four [rows,d] buffers, the fp32 residual stream [rows,d] and one [rows,F] buffer
+    assert fv.fvar_block_workspace_bytes(r, 2, 10) == 4 * 5120 + 10240 + 10240
     assert fv.fvar_select_workspace_bytes(r, 3, 100) == 1280
 
 

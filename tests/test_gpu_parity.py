@@ -244,3 +244,30 @@ def test_var_d30_full_batch_launch_shape(side):
     assert rel_err(to_np(blk.K[b, Lp:Lp + k]), ref["K_new"][0]) <= 2e-2
     assert rel_err(yk_h[b], ref["y_keep"][0]) <= 2e-2
     assert rel_err(y_h[b], ref["y"][0]) <= 2e-2
+
+
+@pytest.mark.parametrize("name,side,B", [("infinity2b_1024_bf16", 40, 1), ("large_1280_bf16", 40, 1)])
+def test_head_dim_128_workloads_real_shape(name, side, B):
+    """Infinity-2B-shaped (hidden 2048, 16 heads of 128) and large-model-shaped (hidden 4096,
+    32 heads of 128, rank 128) blocks at the 40x40 scale with their real cache prefix (2521 rows):
+    one sample, every output compared with the oracle."""
+    W = wl.WORKLOADS[name]
+    d, H, F, r = W.hidden, W.heads, W.ffn_hidden, W.rank
+    M, Lp, k = W.tokens(side), W.prev_len(side), W.keep(side)
+    x = wl.activations_lowrank(B, M, d, seed=1003, bf16=True)
+    w = wl.block_weights(d, F, seed=2003, bf16=True)
+    Kp, Vp = wl.kv_prefix(B, Lp, H, d // H, seed=3003, bf16=True)
+    Wc, Gc = wl.direct_factors(B, M, r, d, seed=4003, bf16=True)
+    blk = GpuBlock(d, H, F, "bf16", w, Kp, Vp, Lp + M)
+    xd = to_dev(x, "bf16")
+    s, keep, drop = blk.score_select(xd, k)
+    y_keep = blk.pruned(xd, keep, k)
+    y = blk.fill(y_keep, keep, drop, M, to_dev(Wc, "bf16"), to_dev(Gc, "bf16"))
+    torch.cuda.synchronize()
+    ref = oracle_pruned(x, k, w, H, Kp, Vp, Wc, Gc)
+    same_scores_or_xfail(s, keep, drop, x, k, ref)
+    assert np.array_equal(keep.cpu().numpy(), ref["idx_keep"])
+    assert rel_err(to_np(blk.K[:, Lp:Lp + k]), ref["K_new"]) <= 2e-2
+    assert rel_err(to_np(blk.V[:, Lp:Lp + k]), ref["V_new"]) <= 2e-2
+    assert rel_err(to_np(y_keep), ref["y_keep"]) <= 2e-2
+    assert rel_err(to_np(y), ref["y"]) <= 2e-2
