@@ -125,6 +125,9 @@ SMALL = [  # dtype, B, M, d, H, F, Lp, k, r
     ("bf16", 1, 200, 384, 6, 768, 500, 200, 24),     # keep everything
     ("f32", 2, 96, 128, 2, 256, 37, 40, 16),
     ("f32", 1, 150, 256, 2, 512, 65, 33, 8),         # head_dim 128
+    ("bf16", 2, 130, 192, 3, 448, 0, 67, 16),        # empty cache prefix: only the new rows are keys
+    ("bf16", 3, 520, 256, 2, 1024, 300, 257, 64),    # head_dim 128, several samples, k just over a tile
+    ("f32", 1, 64, 64, 1, 64, 0, 64, 4),             # smallest geometry, nothing cached, keep all
 ]
 
 
