@@ -57,6 +57,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
     const int rl = lane & 31, g = lane >> 5;
     const int h = blockIdx.y, b = blockIdx.z;
     const int q0 = blockIdx.x * (128 * NQ) + wave * (32 * NQ);
+    const bool wave_active = __builtin_amdgcn_readfirstlane(q0 < n ? 1 : 0) != 0;
     const size_t rowpitch = (size_t)H * DH;
     const uint16_t *Kb = Kc + ((size_t)b * cap * H + h) * DH;
     const uint16_t *Vb = Vc + ((size_t)b * cap * H + h) * DH;
@@ -181,6 +182,8 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
         load_tile((it + 1) * BT);
         __builtin_amdgcn_sched_barrier(0);
 
+        // a wavefront whose queries all lie past the end only helps with the staging
+        if (wave_active) {
         // ---- S^T = K Q^T : [64 keys] x [32*NQ queries]
         floatx16_t sacc[2][NQ];
 #pragma unroll
@@ -268,6 +271,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
                     oacc[db][j] =
                         __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u][j], oacc[db][j], 0, 0, 0);
             }
+        }
         }
         wait_tile();
         store_tile(lds + ((it + 1) & 1) * STAGE);
