@@ -35,6 +35,16 @@ __device__ __forceinline__ intx4_t global_load_b128(const void *base, uint32_t b
     return v;
 }
 
+// Chunk swizzle of the V^T tile (rows = head-dim index, 8 chunks of 8 keys).  Readers fetch 16
+// consecutive rows at one logical chunk: (row/2)%8 makes those 16 accesses cover all 64 banks
+// once, and the extra term is constant inside an aligned group of 16 rows, so it keeps that.
+// Writers store 8-byte halves to rows 8 apart (one per 8-column block of the transposed 4x8
+// blocks): the extra term, a function of row/16, spreads those rows over different chunks.
+__device__ __forceinline__ int vt_swz(int row)
+{
+    return ((row >> 1) & 7) ^ (((row >> 4) & 1) << 2) ^ ((row >> 5) & 3);
+}
+
 template <int DH, int NQ>
 __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(const uint16_t *__restrict__ q,
                                                         const uint16_t *__restrict__ Kc,
@@ -145,9 +155,13 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
                 lo.y = __builtin_amdgcn_perm(vreg[i][3][m], vreg[i][2][m], 0x05040100u);
                 hi.x = __builtin_amdgcn_perm(vreg[i][1][m], vreg[i][0][m], 0x07060302u);
                 hi.y = __builtin_amdgcn_perm(vreg[i][3][m], vreg[i][2][m], 0x07060302u);
+                // lanes of odd column blocks store the odd row first: every store instruction then
+                // touches rows of both parities, i.e. both halves of the 64 banks
+                const bool flip = (v_col[i] >> 3) & 1;
                 const int d0 = v_col[i] + 2 * m, d1 = d0 + 1;
-                *reinterpret_cast<uint2 *>(vt + d0 * BT + ((chunk ^ ((d0 >> 1) & 7)) << 3) + sub) = lo;
-                *reinterpret_cast<uint2 *>(vt + d1 * BT + ((chunk ^ ((d1 >> 1) & 7)) << 3) + sub) = hi;
+                const int ra = flip ? d1 : d0, rb = flip ? d0 : d1;
+                *reinterpret_cast<uint2 *>(vt + ra * BT + ((chunk ^ vt_swz(ra)) << 3) + sub) = flip ? hi : lo;
+                *reinterpret_cast<uint2 *>(vt + rb * BT + ((chunk ^ vt_swz(rb)) << 3) + sub) = flip ? lo : hi;
             }
         }
     };
@@ -265,7 +279,7 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
             for (int db = 0; db < DB; ++db) {
                 const int dr = db * 32 + rl;
                 const bf16x8_t vf = *reinterpret_cast<const bf16x8_t *>(
-                    vt + dr * BT + (((2 * u + g) ^ ((dr >> 1) & 7)) << 3));
+                    vt + dr * BT + (((2 * u + g) ^ vt_swz(dr)) << 3));
 #pragma unroll
                 for (int j = 0; j < NQ; ++j)
                     oacc[db][j] =
