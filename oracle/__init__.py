@@ -2,7 +2,8 @@
 
 `fvar_oracle.c` holds the plain loops; this module compiles it with gcc, loads
 it through ctypes and wraps it for numpy arrays.  `factors.py` builds the
-rank-r factors of the cached feature in fp64 numpy.  Nothing here imports or
+rank-r factors of the cached feature in fp64 numpy and `rp_path.py` the random-projection
+input variant of the fidelity-refinement stage.  Nothing here imports or
 is imported by the GPU package; only tests, the smoke check and the
 benchmark's CPU-baseline leg use it.
 """

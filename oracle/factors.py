@@ -57,6 +57,25 @@ def cache_factors(C: np.ndarray, z: np.ndarray, ridge: float = 0.0):
     return W.astype(np.float32), G.astype(np.float32)
 
 
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even to bfloat16 precision, returned as fp32."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(a))
+
+
+def stored_factors(C: np.ndarray, Q: np.ndarray, ridge: float = 0.0, bf16: bool = False):
+    """(W_c, G_c) when the factors are kept in the storage type of the cache.
+
+    G_c = store(Q^T C) is what the restoration W_c G_c will later be computed from, so the
+    least-squares problem of Eq. "lstsq" is posed against that stored G_c (not the unrounded
+    product): W_c = store(C G_c^T (G_c G_c^T)^{-1}).  store() rounds to bf16 or to fp32."""
+    store = round_bf16 if bf16 else (lambda a: np.asarray(a, np.float32))
+    G = store(project(Q, C))
+    W = restoration_matrix(G, C, ridge)
+    return store(W), G
+
+
 def energy_rank(C: np.ndarray, alpha: float) -> int:
     """Smallest r with eta_r = sum_{i<=r} sigma_i^2 / sum_i sigma_i^2 >= alpha (Eq. "low_rank_percent")."""
     sv = np.linalg.svd(np.asarray(C, np.float64), compute_uv=False)

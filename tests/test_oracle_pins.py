@@ -395,3 +395,106 @@ def test_random_projection_preserves_norm_in_expectation():
     assert abs(vals.mean() - 1.0) < 3 * np.sqrt(2.0 / r / trials)
     Q = factors.random_projection_matrix(wl.normal_draws(1, 4000, r, seed=5)[0], r)
     assert abs(Q.var() * r - 1.0) < 0.02
+
+
+# ----------------------------------------------------------------------------- RP input path
+def test_round_bf16_matches_library_cast():
+    rng = np.random.default_rng(3)
+    a = (rng.standard_normal(4096) * np.exp(rng.uniform(-20, 20, 4096))).astype(np.float32)
+    a[:4] = [0.0, -0.0, 1.00390625, 1.01171875]      # the last two sit exactly between neighbours
+    ref = torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(factors.round_bf16(a), ref)
+    assert factors.round_bf16(a[2:4]).tolist() == [1.0, 1.015625]      # ties go to the even mantissa
+
+
+def test_rp_input_is_qt_times_x():
+    from oracle import rp_path
+    M, d, r = 23, 16, 5
+    rng = np.random.default_rng(4)
+    X = rng.standard_normal((M, d)); Y = rng.standard_normal((M, d))
+    Q = factors.random_projection_matrix(wl.normal_draws(1, M, r, seed=21)[0], r)
+    F = rp_path.rp_input(Q, X)
+    assert F.shape == (r, d) and F.dtype == np.float32
+    # written out element by element: F[t,j] = sum_i Q[i,t] X[i,j]  (catches a transposed operand)
+    brute = np.array([[sum(Q[i, t] * X[i, j] for i in range(M)) for j in range(d)] for t in range(r)])
+    assert np.abs(F - brute).max() < 1e-6
+    # linear in X
+    lin = rp_path.rp_input(Q, 2.0 * X - 3.0 * Y)
+    assert np.abs(lin - (2.0 * F - 3.0 * rp_path.rp_input(Q, Y))).max() < 1e-5
+    # a column-selection Q turns the projection into the row gather of the token-selection path
+    idx = np.array([2, 7, 11, 19, 22])
+    S = np.zeros((M, r)); S[idx, np.arange(r)] = 1.0
+    assert np.array_equal(rp_path.rp_input(S, X), X[idx].astype(np.float32))
+    # storage rounding
+    assert np.array_equal(rp_path.rp_input(Q, X, bf16=True), factors.round_bf16(F64 := factors.project(Q, X)))
+    assert np.abs(rp_path.rp_input(Q, X, bf16=True) - F64).max() <= np.abs(F64).max() * 2.0 ** -8
+
+
+def test_cache_fill_is_eq_redefine():
+    from oracle import rp_path
+    M, d = 9, 4
+    Cm = np.arange(M * d, dtype=np.float32).reshape(M, d)
+    keep = np.array([1, 4, 8], np.int32)
+    yk = -np.ones((3, d), np.float32) * np.array([[1.0], [2.0], [3.0]], np.float32)
+    Y = rp_path.cache_fill(yk, keep, Cm)
+    for i in range(M):
+        if i in keep.tolist():
+            assert np.array_equal(Y[i], yk[keep.tolist().index(i)])
+        else:
+            assert np.array_equal(Y[i], Cm[i])
+    assert np.array_equal(rp_path.cache_fill(np.zeros((0, d), np.float32), np.zeros(0, np.int32), Cm), Cm)
+    full = np.arange(M, dtype=np.int32)
+    assert np.array_equal(rp_path.cache_fill(2 * Cm, full, Cm), 2 * Cm)
+    # the rank-r fill at full rank restores exactly these rows (Eq. "redefine" with the raw cache)
+    C2 = wl.cached_feature(1, 12, 20, 12, seed=13, noise=0.3)[0]
+    Wc, Gc = factors.cache_factors(C2, wl.normal_draws(1, 12, 12, seed=14)[0])
+    keep2 = np.array([0, 5], np.int32); drop2 = np.array([i for i in range(12) if i not in (0, 5)], np.int32)
+    yk2 = np.ones((2, 20), np.float32)
+    a = oracle.lowrank_fill(yk2, keep2, drop2, 12, Wc, Gc)
+    b = rp_path.cache_fill(yk2, keep2, C2)
+    assert np.abs(a - b).max() < 1e-4 * np.abs(C2).max()
+
+
+def test_rp_step_with_selection_matrix_equals_token_selection_path():
+    from oracle import rp_path
+    x, w, H, Kp, Vp, Cm, Wc, Gc = _small_case(seed=7, noise=0.05)
+    M, d = x.shape; Lp = Kp.shape[0]; r = 6
+    keep, drop = oracle.topk(oracle.scores(x), r)
+    S = np.zeros((M, r)); S[keep, np.arange(r)] = 1.0
+    Kq, Vq = _cache(Kp, Vp, r)
+    ref = oracle.pruned_step(x, r, w, H, Kq, Vq, Lp, Wc, Gc)
+    Kr, Vr = _cache(Kp, Vp, r)
+    out = rp_path.rp_step(x, S, Cm, w, H, Kr, Vr, Lp)
+    assert np.array_equal(out["idx_keep"], ref["idx_keep"]) and np.array_equal(out["idx_drop"], ref["idx_drop"])
+    assert np.array_equal(out["y_keep"], ref["y_keep"])
+    assert np.array_equal(Kr, Kq) and np.array_equal(Vr, Vq)
+    assert np.array_equal(out["y"][keep], ref["y_keep"]) and np.array_equal(out["y"][drop], Cm[drop])
+    # a Gaussian Q: the block sees r mixed rows; the output keeps the cached rows elsewhere
+    Q = factors.random_projection_matrix(wl.normal_draws(1, M, r, seed=31)[0], r)
+    Kg, Vg = _cache(Kp, Vp, r)
+    g = rp_path.rp_step(x, Q, Cm, w, H, Kg, Vg, Lp)
+    Kd, Vd = _cache(Kp, Vp, r)
+    direct = oracle.block_forward(rp_path.rp_input(Q, x), w, H, Kd, Vd, Lp)
+    assert np.array_equal(g["y_keep"], direct) and np.array_equal(g["y"][drop], Cm[drop])
+    assert np.array_equal(g["y"][keep], direct)
+
+
+def test_stored_factors_solve_against_the_stored_g():
+    M, d, r = 60, 40, 6
+    Cm = wl.cached_feature(1, M, d, 20, seed=15, noise=0.2)[0]
+    Q = factors.random_projection_matrix(wl.normal_draws(1, M, r, seed=16)[0], r)
+    W0, G0 = factors.cache_factors(Cm, wl.normal_draws(1, M, r, seed=16)[0])
+    W1, G1 = factors.stored_factors(Cm, Q)
+    assert np.array_equal(G1, G0) and np.abs(W1 - W0).max() < 1e-5 * np.abs(W0).max()
+    # bf16 storage: G is a bf16 value, and W satisfies the normal equations of THAT G
+    Wb, Gb = factors.stored_factors(Cm, Q, bf16=True)
+    assert np.array_equal(Gb, factors.round_bf16(Gb)) and np.array_equal(Wb, factors.round_bf16(Wb))
+    assert np.abs(Gb - G0).max() <= 2.0 ** -8 * np.abs(G0).max()
+    Wex = factors.restoration_matrix(Gb, Cm)
+    G64 = Gb.astype(np.float64)
+    scale = np.abs(Cm).max() * np.abs(G64).max() * d
+    assert np.abs((Cm - Wex @ G64) @ G64.T).max() < 1e-9 * scale
+    assert np.abs(Wb - Wex).max() <= 2.0 ** -8 * np.abs(Wex).max()
+    # solving against the unrounded product instead leaves a visible normal-equation residual
+    Wwrong = factors.restoration_matrix(factors.project(Q, Cm), Cm)
+    assert np.abs((Cm - Wwrong @ G64) @ G64.T).max() > 1e-6 * scale
