@@ -11,7 +11,12 @@
  *     fvar_lowrank_fill          y_keep, idx, W_c,G_c-> y[B,M,d]
  *
  * and fvar_block_forward_dense is the unreduced control (x[B,M,d] -> y[B,M,d],
- * appends M K/V rows).
+ * appends M K/V rows).  fvar_cache_factors builds W_c, G_c from the cached
+ * counterpart feature.  The variant with a random-projection input is
+ *
+ *     fvar_rp_project            Q^T, x[B,M,d]       -> f_r[B,r,d]
+ *     fvar_block_forward_dense   f_r (as r tokens)   -> y_keep[B,r,d]   (appends r K/V rows)
+ *     fvar_cache_fill            y_keep, idx, cache  -> y[B,M,d]
  *
  * Conventions common to every call
  *  - Every tensor pointer is DEVICE memory owned by the caller, row-major,
@@ -153,11 +158,49 @@ fvar_status fvar_block_forward_pruned(fvar_ctx *ctx, fvar_stream stream,
  *   y[b,i,:] = sum_t w_c[b,i,t] * g_c[b,t,:]  if i is in idx_drop[b,:]
  * y_keep:[B,k,d], w_c:[B,M,r], g_c:[B,r,d], y:[B,M,d] (must not overlap y_keep).
  * 1 <= r <= 256, r a multiple of 8 for bf16 (of 4 for fp32).  k == M (idx_drop unused) is a
- * plain scatter.  Accumulation in fp32.  Uses no workspace. */
+ * plain scatter.  Accumulation in fp32.  No workspace. */
 fvar_status fvar_lowrank_fill(fvar_ctx *ctx, fvar_stream stream, const void *y_keep,
                               const int32_t *idx_keep, const int32_t *idx_drop, int32_t B,
                               int32_t M, int32_t k, int32_t r, const void *w_c, const void *g_c,
                               void *y);
+
+/* Random projection to r rows (paper, Sec. "Random Projection (RP) for Low-Rank Feature":
+ * F^_r = Q^T F~ with Q in R^{M x r}, Q_ij ~ N(0, 1/r); Alg. "FasterVAR", fidelity stage).
+ *   out[b,t,:] = sum_i qt[t,i] * x[b,i,:]
+ * qt is Q TRANSPOSED, [rows][M] row-major in the context's element type; the caller draws it
+ * (the library holds no random generator).  q_per_sample != 0: qt is [B][rows][M], one matrix
+ * per sample; otherwise one matrix serves every sample.  x:[B,M,d], out:[B,rows,d], fp32
+ * accumulation.  1 <= rows <= M; M a multiple of 8 for bf16 (of 4 for fp32).  No workspace. */
+fvar_status fvar_rp_project(fvar_ctx *ctx, fvar_stream stream, const void *qt, int32_t q_per_sample,
+                            const void *x, int32_t B, int32_t M, int32_t rows, void *out);
+
+/* Restoration of the full token map with the raw cached rows (paper, Eq. "redefine" as printed,
+ * Alg. "FasterVAR"):
+ *   y[b,i,:] = y_keep[b,j,:]   if i == idx_keep[b,j]
+ *   y[b,i,:] = cache[b,i,:]    if i is in idx_drop[b,:]
+ * y_keep:[B,k,d], cache:[B,M,d] (the cached counterpart feature, already at M rows),
+ * y:[B,M,d].  y may be the very same buffer as cache (then only the kept rows are written,
+ * the pruned rows being in place already); otherwise the buffers must not overlap.
+ * 0 <= k <= M.  No workspace. */
+fvar_status fvar_cache_fill(fvar_ctx *ctx, fvar_stream stream, const void *y_keep,
+                            const int32_t *idx_keep, const int32_t *idx_drop, int32_t B, int32_t M,
+                            int32_t k, const void *cache, void *y);
+
+/* Rank-r factors of the cached counterpart feature (paper, Sec. "Random Projection": G = Q^T C;
+ * Eq. "lstsq" posed on the cached feature as App. "Construction of W_r^o" prescribes):
+ *   g_c[b] = store(qt[b] cache[b])                                   [r,d]
+ *   w_c[b] = store(argmin_W || W g_c[b] - cache[b] ||_F)             [M,r]
+ *          = store((cache g_c^T)(g_c g_c^T + ridge*trace/r*I)^{-1})
+ * store() rounds to the context's element type; the least-squares problem is posed against the
+ * stored g_c.  Gram matrix, Cholesky factorisation and the final product run in fp64.  A Gram
+ * matrix that is not positive definite (r above the rank of the cache with ridge == 0) gives
+ * non-finite w_c; pass a small ridge (e.g. 1e-10) then.  qt, q_per_sample as in fvar_rp_project.
+ * 1 <= r <= min(M,128), r a multiple of 8 for bf16 (of 4 for fp32); M as in fvar_rp_project.
+ * ws: at least fvar_factors_workspace_bytes(ctx,B,M,r). */
+size_t fvar_factors_workspace_bytes(const fvar_ctx *ctx, int32_t B, int32_t M, int32_t r);
+fvar_status fvar_cache_factors(fvar_ctx *ctx, fvar_stream stream, const void *cache, const void *qt,
+                               int32_t q_per_sample, int32_t B, int32_t M, int32_t r, double ridge,
+                               void *w_c, void *g_c, void *ws, size_t ws_bytes);
 
 /* Per-kernel timing (hipEvent pairs around every launch while enabled).  Off by default and
  * outside any throughput measurement.  fvar_profile_read synchronises the recorded events,

@@ -19,7 +19,9 @@ EXPORTS = (
     "fvar_create", "fvar_destroy", "fvar_last_error", "fvar_status_string", "fvar_keep_count",
     "fvar_scale_tokens", "fvar_scale_prev_len", "fvar_select_workspace_bytes",
     "fvar_block_workspace_bytes", "fvar_score_select", "fvar_block_forward_dense",
-    "fvar_block_forward_pruned", "fvar_lowrank_fill", "fvar_profile_enable", "fvar_profile_read",
+    "fvar_block_forward_pruned", "fvar_lowrank_fill", "fvar_rp_project", "fvar_cache_fill",
+    "fvar_factors_workspace_bytes", "fvar_cache_factors", "fvar_profile_enable",
+    "fvar_profile_read",
 )
 
 
@@ -91,6 +93,14 @@ def load_library() -> C.CDLL:
     lib.fvar_block_forward_pruned.restype = C.c_int
     lib.fvar_lowrank_fill.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.fvar_lowrank_fill.restype = C.c_int
+    lib.fvar_rp_project.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, vp]
+    lib.fvar_rp_project.restype = C.c_int
+    lib.fvar_cache_fill.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.fvar_cache_fill.restype = C.c_int
+    lib.fvar_factors_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.fvar_factors_workspace_bytes.restype = sz
+    lib.fvar_cache_factors.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, C.c_double, vp, vp, vp, sz]
+    lib.fvar_cache_factors.restype = C.c_int
     lib.fvar_profile_enable.argtypes = [vp, i32]
     lib.fvar_profile_enable.restype = C.c_int
     lib.fvar_profile_read.argtypes = [vp, C.POINTER(_ProfileEntry), i32]
@@ -219,6 +229,29 @@ def fvar_lowrank_fill(ctx: Context, y_keep, idx_keep, idx_drop, B: int, M: int, 
                       w_c, g_c, y, stream=None) -> None:
     ctx.check(ctx.lib.fvar_lowrank_fill(ctx.handle, _stream(stream), _ptr(y_keep), _ptr(idx_keep),
                                         _ptr(idx_drop), B, M, k, r, _ptr(w_c), _ptr(g_c), _ptr(y)))
+
+
+def fvar_rp_project(ctx: Context, qt, q_per_sample: bool, x, B: int, M: int, rows: int, out,
+                    stream=None) -> None:
+    ctx.check(ctx.lib.fvar_rp_project(ctx.handle, _stream(stream), _ptr(qt), 1 if q_per_sample else 0,
+                                      _ptr(x), B, M, rows, _ptr(out)))
+
+
+def fvar_cache_fill(ctx: Context, y_keep, idx_keep, idx_drop, B: int, M: int, k: int, cache, y,
+                    stream=None) -> None:
+    ctx.check(ctx.lib.fvar_cache_fill(ctx.handle, _stream(stream), _ptr(y_keep), _ptr(idx_keep),
+                                      _ptr(idx_drop), B, M, k, _ptr(cache), _ptr(y)))
+
+
+def fvar_factors_workspace_bytes(ctx: Context, B: int, M: int, r: int) -> int:
+    return ctx.lib.fvar_factors_workspace_bytes(ctx.handle, B, M, r)
+
+
+def fvar_cache_factors(ctx: Context, cache, qt, q_per_sample: bool, B: int, M: int, r: int,
+                       ridge: float, w_c, g_c, ws, stream=None) -> None:
+    ctx.check(ctx.lib.fvar_cache_factors(ctx.handle, _stream(stream), _ptr(cache), _ptr(qt),
+                                         1 if q_per_sample else 0, B, M, r, float(ridge), _ptr(w_c),
+                                         _ptr(g_c), _ptr(ws), _nbytes(ws)))
 
 
 def fvar_profile_enable(ctx: Context, on: bool) -> None:

@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfvar.so")
-SOURCES = ["api.hip", "score_select.hip", "rows.hip", "gemm.hip", "attention.hip", "fill.hip"]
+SOURCES = ["api.hip", "score_select.hip", "rows.hip", "gemm.hip", "attention.hip", "fill.hip",
+           "rp.hip", "factors.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 VALU forms are kept off for every device pass
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

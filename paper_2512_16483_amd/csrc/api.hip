@@ -345,6 +345,103 @@ fvar_status fvar_lowrank_fill(fvar_ctx *c, fvar_stream stream, const void *y_kee
     return launch_status(c, who);
 }
 
+fvar_status fvar_rp_project(fvar_ctx *c, fvar_stream stream, const void *qt, int32_t q_per_sample,
+                            const void *x, int32_t B, int32_t M, int32_t rows, void *out)
+{
+    if (!c) return FVAR_ERR_INVALID_ARG;
+    const char *who = "fvar_rp_project";
+    if (B < 1 || M < 1 || rows < 1 || rows > M)
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: need B>=1 and 1<=rows<=M (B=%d M=%d rows=%d)", who, B,
+                    M, rows);
+    if (!qt || !x || !out) return fail(c, FVAR_ERR_INVALID_ARG, "%s: null argument", who);
+    if (!aligned16(qt) || !aligned16(x) || !aligned16(out))
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: pointer not 16-byte aligned", who);
+    const int mult = c->cfg.dtype == FVAR_BF16 ? 8 : 4;
+    if (M % mult)
+        return fail(c, FVAR_ERR_UNSUPPORTED, "%s: M=%d must be a multiple of %d", who, M, mult);
+    if ((int64_t)B * M > (int64_t)INT32_MAX / 2 || B > 65535)
+        return fail(c, FVAR_ERR_UNSUPPORTED, "%s: B or B*M too large", who);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    timed(c, st, "rp_project", [&] {
+        fvar::launch_rp_project(dtype(c), qt, q_per_sample ? (size_t)rows * M : 0, x, B, M, rows,
+                                c->cfg.hidden, out, st);
+    });
+    return launch_status(c, who);
+}
+
+fvar_status fvar_cache_fill(fvar_ctx *c, fvar_stream stream, const void *y_keep,
+                            const int32_t *idx_keep, const int32_t *idx_drop, int32_t B, int32_t M,
+                            int32_t k, const void *cache, void *y)
+{
+    if (!c) return FVAR_ERR_INVALID_ARG;
+    const char *who = "fvar_cache_fill";
+    if (B < 1 || M < 1 || k < 0 || k > M)
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: need B>=1 and 0<=k<=M (B=%d M=%d k=%d)", who, B, M, k);
+    if (!y || (k > 0 && (!y_keep || !idx_keep)))
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: null output, y_keep or idx_keep", who);
+    if (k < M && (!idx_drop || !cache))
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: idx_drop and cache are required when k < M", who);
+    if (!aligned16(y) || !aligned16(y_keep) || !aligned16(cache))
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: pointer not 16-byte aligned", who);
+    if ((int64_t)B * M > (int64_t)INT32_MAX / 2)
+        return fail(c, FVAR_ERR_UNSUPPORTED, "%s: B*M too large", who);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    timed(c, st, "cache_fill", [&] {
+        fvar::launch_cache_fill(dtype(c), y_keep, idx_keep, idx_drop, B, M, k, c->cfg.hidden, cache, y,
+                                st);
+    });
+    return launch_status(c, who);
+}
+
+size_t fvar_factors_workspace_bytes(const fvar_ctx *c, int32_t B, int32_t M, int32_t r)
+{
+    if (!c || B < 1 || M < 1 || r < 1) return 0;
+    return align256((size_t)B * M * r * sizeof(float)) + 2 * align256((size_t)B * r * r * sizeof(double));
+}
+
+fvar_status fvar_cache_factors(fvar_ctx *c, fvar_stream stream, const void *cache, const void *qt,
+                               int32_t q_per_sample, int32_t B, int32_t M, int32_t r, double ridge,
+                               void *w_c, void *g_c, void *ws, size_t ws_bytes)
+{
+    if (!c) return FVAR_ERR_INVALID_ARG;
+    const char *who = "fvar_cache_factors";
+    const int mult = c->cfg.dtype == FVAR_BF16 ? 8 : 4;
+    if (B < 1 || M < 1 || r < 1 || r > M)
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: need B>=1 and 1<=r<=M (B=%d M=%d r=%d)", who, B, M, r);
+    if (!cache || !qt || !w_c || !g_c) return fail(c, FVAR_ERR_INVALID_ARG, "%s: null argument", who);
+    if (!(ridge >= 0.0)) return fail(c, FVAR_ERR_INVALID_ARG, "%s: ridge must be >= 0", who);
+    if (r > 128 || r % mult)
+        return fail(c, FVAR_ERR_UNSUPPORTED, "%s: rank %d must be <= 128 and a multiple of %d", who, r,
+                    mult);
+    if (M % mult)
+        return fail(c, FVAR_ERR_UNSUPPORTED, "%s: M=%d must be a multiple of %d", who, M, mult);
+    if ((int64_t)B * M > (int64_t)INT32_MAX / 2 || B > 65535)
+        return fail(c, FVAR_ERR_UNSUPPORTED, "%s: B or B*M too large", who);
+    if (!aligned16(cache) || !aligned16(qt) || !aligned16(w_c) || !aligned16(g_c) || !aligned16(ws))
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: pointer not 16-byte aligned", who);
+    const size_t need = fvar_factors_workspace_bytes(c, B, M, r);
+    if (!ws || ws_bytes < need)
+        return fail(c, FVAR_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need,
+                    ws_bytes);
+    char *p = static_cast<char *>(ws);
+    float *T = reinterpret_cast<float *>(p);
+    p += align256((size_t)B * M * r * sizeof(float));
+    double *S = reinterpret_cast<double *>(p);
+    p += align256((size_t)B * r * r * sizeof(double));
+    double *Sinv = reinterpret_cast<double *>(p);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const DType dt = dtype(c);
+    const int d = c->cfg.hidden;
+    timed(c, st, "factor_project", [&] {
+        fvar::launch_rp_project(dt, qt, q_per_sample ? (size_t)r * M : 0, cache, B, M, r, d, g_c, st);
+    });
+    timed(c, st, "factor_t", [&] { fvar::launch_factor_t(dt, cache, g_c, B, M, r, d, T, st); });
+    timed(c, st, "factor_gram", [&] { fvar::launch_factor_gram(dt, g_c, B, r, d, S, st); });
+    timed(c, st, "factor_inverse", [&] { fvar::launch_factor_inverse(S, B, r, ridge, Sinv, st); });
+    timed(c, st, "factor_w", [&] { fvar::launch_factor_w(dt, T, Sinv, B, M, r, w_c, st); });
+    return launch_status(c, who);
+}
+
 fvar_status fvar_profile_enable(fvar_ctx *c, int32_t on)
 {
     if (!c) return FVAR_ERR_INVALID_ARG;

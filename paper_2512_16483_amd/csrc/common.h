@@ -144,4 +144,22 @@ void launch_fill(DType dt, const void *y_keep, const int32_t *idx_keep, const in
                  int B, int M, int k, int r, int d, const void *w_c, const void *g_c, void *y,
                  hipStream_t st);
 
+// raw-cache variant of the fill: pruned rows are copied from cache:[B,M,d]
+void launch_cache_fill(DType dt, const void *y_keep, const int32_t *idx_keep, const int32_t *idx_drop,
+                       int B, int M, int k, int d, const void *cache, void *y, hipStream_t st);
+
+// out[b] = qt[b] x[b]:  qt:[rows,M] (sample stride q_stride elements, 0 = shared), x:[B,M,d],
+// out:[B,rows,d].  M must be a multiple of the 16-byte chunk (8 bf16 / 4 fp32 elements).
+void launch_rp_project(DType dt, const void *qt, size_t q_stride, const void *x, int B, int M,
+                       int rows, int d, void *out, hipStream_t st);
+
+// restoration matrix W_c = (C G_c^T)(G_c G_c^T)^{-1} in four steps; T:[B,M,r] fp32,
+// S, Sinv:[B,r,r] fp64 are scratch.  r <= 128.
+void launch_factor_t(DType dt, const void *cache, const void *g_c, int B, int M, int r, int d, float *T,
+                     hipStream_t st);
+void launch_factor_gram(DType dt, const void *g_c, int B, int r, int d, double *S, hipStream_t st);
+void launch_factor_inverse(const double *S, int B, int r, double ridge, double *Sinv, hipStream_t st);
+void launch_factor_w(DType dt, const float *T, const double *Sinv, int B, int M, int r, void *w_c,
+                     hipStream_t st);
+
 }  // namespace fvar

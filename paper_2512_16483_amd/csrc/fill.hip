@@ -188,6 +188,51 @@ __global__ __launch_bounds__(256) void fill_f32_kernel(const float *__restrict__
     }
 }
 
+// ------------------------------------------------------------------ raw cached rows
+// Eq. "redefine" as printed: kept rows come from the block output, every other row is the cached
+// counterpart row itself.  One wavefront per output row: the first B*k rows of the launch scatter
+// y_keep, the remaining B*(M-k) copy row idx_drop[b,j] of the cache to the same position of y.
+template <typename T>
+__global__ __launch_bounds__(256) void cache_fill_kernel(const T *__restrict__ y_keep,
+                                                         const int32_t *__restrict__ idx_keep,
+                                                         const int32_t *__restrict__ idx_drop, int M,
+                                                         int k, int B, int d,
+                                                         const T *__restrict__ cache,
+                                                         T *__restrict__ y)
+{
+    constexpr int E = Elem<T>::kPerChunk;
+    const int kept_blocks = (B * k + 3) / 4;
+    if ((int)blockIdx.x < kept_blocks) {
+        scatter_rows<T>(blockIdx.x, y_keep, idx_keep, M, k, B * k, d, y);
+        return;
+    }
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int nd = M - k;
+    const int j = (blockIdx.x - kept_blocks) * 4 + wave;
+    if (j >= B * nd) return;                       // also covers nd == 0
+    const int b = j / nd;
+    const size_t row = (size_t)b * M + idx_drop[j];
+    const uint4 *src = reinterpret_cast<const uint4 *>(cache + row * d);
+    uint4 *dst = reinterpret_cast<uint4 *>(y + row * d);
+    const int nchunk = d / E;
+    for (int c = lane; c < nchunk; c += 64) dst[c] = src[c];
+}
+
+void launch_cache_fill(DType dt, const void *y_keep, const int32_t *idx_keep, const int32_t *idx_drop,
+                       int B, int M, int k, int d, const void *cache, void *y, hipStream_t st)
+{
+    // cache == y: the pruned rows are in place already and only the kept rows are written
+    const int copy_rows = cache == y ? 0 : B * (M - k);
+    const int blocks = (B * k + 3) / 4 + (copy_rows + 3) / 4;
+    if (blocks == 0) return;
+    if (dt == DType::BF16)
+        launch(cache_fill_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t *)y_keep,
+               idx_keep, idx_drop, M, k, B, d, (const uint16_t *)cache, (uint16_t *)y);
+    else
+        launch(cache_fill_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float *)y_keep, idx_keep,
+               idx_drop, M, k, B, d, (const float *)cache, (float *)y);
+}
+
 void launch_fill(DType dt, const void *y_keep, const int32_t *idx_keep, const int32_t *idx_drop,
                  int B, int M, int k, int r, int d, const void *w_c, const void *g_c, void *y,
                  hipStream_t st)

@@ -99,6 +99,26 @@ def test_entry_points_reject_bad_arguments_without_launching():
     assert lib.fvar_lowrank_fill(h, None, fake, fake, None, 1, 10, 5, 16, fake, fake, fake) == fv.FVAR_ERR_INVALID_ARG
     assert lib.fvar_lowrank_fill(h, None, fake, fake, fake, 1, 10, 11, 16, fake, fake, fake) == fv.FVAR_ERR_INVALID_ARG
     assert lib.fvar_status_string(fv.FVAR_ERR_WORKSPACE) == b"workspace too small"
+    # random projection: rows in [1,M], M a multiple of 8 for bf16, pointers present and aligned
+    assert lib.fvar_rp_project(h, None, fake, 0, fake, 1, 16, 17, fake) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_rp_project(h, None, fake, 0, fake, 1, 16, 0, fake) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_rp_project(h, None, None, 0, fake, 1, 16, 4, fake) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_rp_project(h, None, fake + 4, 0, fake, 1, 16, 4, fake) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_rp_project(h, None, fake, 0, fake, 1, 12, 4, fake) == fv.FVAR_ERR_UNSUPPORTED
+    # raw-cache fill: the cache and the pruned index list are required when rows are pruned
+    assert lib.fvar_cache_fill(h, None, fake, fake, fake, 1, 10, 11, fake, fake) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_cache_fill(h, None, fake, fake, None, 1, 10, 5, fake, fake) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_cache_fill(h, None, fake, fake, fake, 1, 10, 5, None, fake) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_cache_fill(h, None, None, fake, fake, 1, 10, 5, fake, fake) == fv.FVAR_ERR_INVALID_ARG
+    # factors: rank limits, ridge sign, workspace
+    need = fv.fvar_factors_workspace_bytes(c, 2, 64, 16)
+    assert need == 2 * 64 * 16 * 4 + 2 * (2 * 16 * 16 * 8)
+    assert lib.fvar_cache_factors(h, None, fake, fake, 0, 2, 64, 136, 0.0, fake, fake, fake, 1 << 30) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_cache_factors(h, None, fake, fake, 0, 2, 256, 136, 0.0, fake, fake, fake, 1 << 30) == fv.FVAR_ERR_UNSUPPORTED
+    assert lib.fvar_cache_factors(h, None, fake, fake, 0, 2, 64, 12, 0.0, fake, fake, fake, 1 << 30) == fv.FVAR_ERR_UNSUPPORTED
+    assert lib.fvar_cache_factors(h, None, fake, fake, 0, 2, 64, 16, -1.0, fake, fake, fake, 1 << 30) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_cache_factors(h, None, fake, fake, 0, 2, 64, 16, 0.0, fake, None, fake, 1 << 30) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_cache_factors(h, None, fake, fake, 0, 2, 64, 16, 0.0, fake, fake, fake, need - 1) == fv.FVAR_ERR_WORKSPACE
 
 
 def test_missing_library_fails_loudly(monkeypatch):

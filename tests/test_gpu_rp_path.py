@@ -1,0 +1,226 @@
+"""GPU parity of the random-projection input path and of the on-GPU factor construction: the HIP
+kernels through the C ABI against the CPU oracle on the same seeded inputs.
+
+Bars as for the main path: copies and index work bit-exact; bf16 outputs within 2e-2, fp32
+outputs within 1e-4, measured as max_i |g_i - o_i| / max(|o_i|, rms(o))."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import factors, rp_path
+import paper_2512_16483_amd as fv
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+from gpu_util import TOL, GpuBlock, rel_err, tdtype, to_dev, to_np  # noqa: E402
+
+
+def _ctx(d, dtype, H=None):
+    H = H or d // 64
+    return fv.Context(hidden=d, heads=H, head_dim=d // H, ffn_hidden=4 * d, dtype=dtype)
+
+
+def _q(B, M, r, seed, dtype, per_sample):
+    """Q = z / sqrt(r) in the storage type, [B or 1, M, r]."""
+    z = wl.normal_draws(B if per_sample else 1, M, r, seed=seed)
+    Q = (z / np.sqrt(float(r))).astype(np.float32)
+    return wl.round_to_bf16(Q) if dtype == "bf16" else Q
+
+
+def _qt_dev(Q, dtype):
+    return to_dev(np.ascontiguousarray(np.swapaxes(Q, 1, 2)), dtype)      # [B or 1, r, M]
+
+
+# ----------------------------------------------------------------------------- projection
+@pytest.mark.parametrize("dtype,B,M,rows,d,per_sample", [
+    ("bf16", 2, 72, 5, 128, False),          # one full chunk of 64 tokens + a ragged one
+    ("bf16", 3, 200, 130, 192, True),        # two row tiles, ragged rows, ragged column tile
+    ("bf16", 1, 576, 231, 1920, False),      # scale 24 of the depth-30 model
+    ("bf16", 2, 1024, 64, 256, True),
+    ("bf16", 1, 8, 1, 64, False),            # minimal
+    ("f32", 2, 36, 7, 64, True),
+    ("f32", 1, 256, 32, 1024, False),        # the fp32 configuration
+])
+def test_rp_project_parity(dtype, B, M, rows, d, per_sample):
+    x = wl.activations_lowrank(B, M, d, seed=50 + M, bf16=dtype == "bf16")
+    Q = _q(B, M, rows, 60 + M, dtype, per_sample)
+    ctx = _ctx(d, dtype)
+    out = torch.full((B, rows, d), float("nan"), dtype=tdtype(dtype), device="cuda")
+    fv.fvar_rp_project(ctx, _qt_dev(Q, dtype), per_sample, to_dev(x, dtype), B, M, rows, out)
+    torch.cuda.synchronize()
+    got = to_np(out)
+    for b in range(B):
+        ref = rp_path.rp_input(Q[b if per_sample else 0], x[b], bf16=dtype == "bf16")
+        assert rel_err(got[b], ref) <= TOL[dtype], (b, rel_err(got[b], ref))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rp_project_with_selection_matrix_is_the_gather(dtype):
+    # products with 1 and 0 are exact, so a column-selection Q must reproduce the rows bit for bit
+    B, M, rows, d = 2, 136, 40, 192
+    x = wl.activations_iid(B, M, d, seed=71, bf16=dtype == "bf16")
+    rng = np.random.default_rng(5)
+    Q = np.zeros((B, M, rows), np.float32)
+    idx = np.stack([np.sort(rng.choice(M, rows, replace=False)) for _ in range(B)])
+    for b in range(B):
+        Q[b, idx[b], np.arange(rows)] = 1.0
+    ctx = _ctx(d, dtype)
+    out = torch.empty((B, rows, d), dtype=tdtype(dtype), device="cuda")
+    fv.fvar_rp_project(ctx, _qt_dev(Q, dtype), True, to_dev(x, dtype), B, M, rows, out)
+    torch.cuda.synchronize()
+    for b in range(B):
+        assert np.array_equal(to_np(out[b]), x[b][idx[b]])
+
+
+# ----------------------------------------------------------------------------- raw-cache fill
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,M,k,d", [(2, 37, 11, 128), (1, 64, 0, 64), (3, 50, 50, 192), (2, 576, 231, 1920)])
+def test_cache_fill_bitexact(dtype, B, M, k, d):
+    bf = dtype == "bf16"
+    Cm = wl.activations_iid(B, M, d, seed=81, bf16=bf)
+    yk = wl.activations_iid(B, max(k, 1), d, seed=82, bf16=bf)[:, :k]
+    rng = np.random.default_rng(M + k)
+    keep = np.stack([np.sort(rng.choice(M, k, replace=False)) for _ in range(B)]).astype(np.int32).reshape(B, k)
+    drop = np.stack([np.setdiff1d(np.arange(M), keep[b]) for b in range(B)]).astype(np.int32).reshape(B, M - k)
+    ctx = _ctx(d, dtype)
+    kd, dd = torch.from_numpy(keep).cuda(), torch.from_numpy(drop).cuda()
+    ykd, Cd = to_dev(yk, dtype), to_dev(Cm, dtype)
+    y = torch.full((B, M, d), float("nan"), dtype=tdtype(dtype), device="cuda")
+    fv.fvar_cache_fill(ctx, ykd if k else None, kd if k else None, dd if k < M else None, B, M, k,
+                       Cd if k < M else None, y)
+    # in place: the cache buffer itself receives the kept rows
+    Cin = Cd.clone()
+    fv.fvar_cache_fill(ctx, ykd if k else None, kd if k else None, dd if k < M else None, B, M, k,
+                       Cin, Cin)
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref = rp_path.cache_fill(yk[b], keep[b], Cm[b])
+        assert np.array_equal(to_np(y[b]), ref)
+        assert np.array_equal(to_np(Cin[b]), ref)
+
+
+# ----------------------------------------------------------------------------- factors
+@pytest.mark.parametrize("dtype,B,M,d,r,rank,noise,per_sample", [
+    ("bf16", 2, 72, 128, 8, 24, 0.1, True),
+    ("bf16", 1, 200, 192, 40, 60, 0.1, False),       # r not a multiple of 32, ragged row block
+    ("bf16", 2, 576, 1920, 64, 102, 0.1, False),     # depth-30 geometry, scale 24
+    ("bf16", 1, 256, 256, 128, 200, 0.1, False),     # largest rank
+    ("bf16", 1, 64, 64, 16, 16, 0.0, False),         # exactly rank r: lossless
+    ("f32", 2, 36, 64, 8, 12, 0.1, True),
+    ("f32", 1, 256, 1024, 32, 32, 0.05, False),      # the fp32 configuration
+])
+def test_cache_factors_parity(dtype, B, M, d, r, rank, noise, per_sample):
+    bf = dtype == "bf16"
+    Cm = wl.cached_feature(B, M, d, rank, seed=90 + M, noise=noise)
+    if bf:
+        Cm = wl.round_to_bf16(Cm)
+    Q = _q(B, M, r, 91 + M, dtype, per_sample)
+    ctx = _ctx(d, dtype)
+    Cd = to_dev(Cm, dtype)
+    w_c = torch.full((B, M, r), float("nan"), dtype=tdtype(dtype), device="cuda")
+    g_c = torch.full((B, r, d), float("nan"), dtype=tdtype(dtype), device="cuda")
+    ws = torch.empty(fv.fvar_factors_workspace_bytes(ctx, B, M, r), dtype=torch.uint8, device="cuda")
+    fv.fvar_cache_factors(ctx, Cd, _qt_dev(Q, dtype), per_sample, B, M, r, 0.0, w_c, g_c, ws)
+    torch.cuda.synchronize()
+    Wg, Gg = to_np(w_c), to_np(g_c)
+    for b in range(B):
+        Wo, Go = factors.stored_factors(Cm[b], Q[b if per_sample else 0], bf16=bf)
+        assert rel_err(Gg[b], Go) <= TOL[dtype], ("G", b, rel_err(Gg[b], Go))
+        assert rel_err(Wg[b], Wo) <= TOL[dtype], ("W", b, rel_err(Wg[b], Wo))
+        # the restoration the factors exist for: as close to C as the oracle's
+        C64 = Cm[b].astype(np.float64)
+        res_g = np.linalg.norm(Wg[b].astype(np.float64) @ Gg[b].astype(np.float64) - C64)
+        res_o = np.linalg.norm(Wo.astype(np.float64) @ Go.astype(np.float64) - C64)
+        assert res_g <= res_o * 1.02 + (4e-3 if bf else 1e-6) * np.linalg.norm(C64)
+        if noise == 0.0:       # rank r exactly (up to the bf16 rounding of C, W and G themselves)
+            assert res_g <= (2e-2 if bf else 1e-5) * np.linalg.norm(C64)
+
+
+def test_cache_factors_feed_the_fill():
+    # factors built on the GPU, used by the rank-r fill, against the oracle's fill of its factors
+    dtype, B, M, d, r, k = "bf16", 2, 144, 256, 32, 58
+    Cm = wl.round_to_bf16(wl.cached_feature(B, M, d, 40, seed=95, noise=0.05))
+    Q = _q(B, M, r, 96, dtype, False)
+    ctx = _ctx(d, dtype)
+    w_c = torch.empty((B, M, r), dtype=torch.bfloat16, device="cuda")
+    g_c = torch.empty((B, r, d), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(fv.fvar_factors_workspace_bytes(ctx, B, M, r), dtype=torch.uint8, device="cuda")
+    fv.fvar_cache_factors(ctx, to_dev(Cm, dtype), _qt_dev(Q, dtype), False, B, M, r, 0.0, w_c, g_c, ws)
+    rng = np.random.default_rng(1)
+    keep = np.stack([np.sort(rng.choice(M, k, replace=False)) for _ in range(B)]).astype(np.int32)
+    drop = np.stack([np.setdiff1d(np.arange(M), keep[b]) for b in range(B)]).astype(np.int32)
+    yk = wl.activations_iid(B, k, d, seed=97, bf16=True)
+    y = torch.empty((B, M, d), dtype=torch.bfloat16, device="cuda")
+    fv.fvar_lowrank_fill(ctx, to_dev(yk, dtype), torch.from_numpy(keep).cuda(), torch.from_numpy(drop).cuda(),
+                         B, M, k, r, w_c, g_c, y)
+    torch.cuda.synchronize()
+    for b in range(B):
+        Wo, Go = factors.stored_factors(Cm[b], Q[0], bf16=True)
+        ref = oracle.lowrank_fill(yk[b], keep[b], drop[b], M, Wo, Go)
+        assert rel_err(to_np(y[b]), ref) <= TOL[dtype]
+
+
+# ----------------------------------------------------------------------------- whole RP step
+def _rp_case(dtype, B, M, r, d, H, Lp, seed):
+    bf = dtype == "bf16"
+    x = wl.activations_lowrank(B, M, d, seed=seed, bf16=bf)
+    w = wl.block_weights(d, 4 * d, seed=seed + 1, bf16=bf, std=0.8 / np.sqrt(d))
+    Kp, Vp = wl.kv_prefix(B, Lp, H, d // H, seed=seed + 2, bf16=bf)
+    Cm = wl.cached_feature(B, M, d, max(8, r), seed=seed + 3, noise=0.05)
+    if bf:
+        Cm = wl.round_to_bf16(Cm)
+    Q = _q(B, M, r, seed + 4, dtype, False)
+    return x, w, Kp, Vp, Cm, Q
+
+
+@pytest.mark.parametrize("dtype,B,M,r,d,H,Lp", [
+    ("bf16", 2, 144, 58, 256, 4, 100),
+    ("bf16", 1, 200, 64, 256, 2, 77),        # head_dim 128
+    ("f32", 1, 64, 16, 128, 2, 40),
+    ("f32", 1, 256, 128, 1024, 16, 424),     # the fp32 configuration with the projected input
+])
+def test_rp_step_parity(dtype, B, M, r, d, H, Lp):
+    x, w, Kp, Vp, Cm, Q = _rp_case(dtype, B, M, r, d, H, Lp, seed=300 + M)
+    blk = GpuBlock(d, H, 4 * d, dtype, w, Kp, Vp, Lp + r)
+    xd = to_dev(x, dtype)
+    f_r = torch.empty((B, r, d), dtype=tdtype(dtype), device="cuda")
+    fv.fvar_rp_project(blk.ctx, _qt_dev(Q, dtype), False, xd, B, M, r, f_r)
+    y_keep = blk.dense(f_r)                                  # the r projected rows are the block's tokens
+    s, keep, drop = blk.score_select(xd, r)
+    y = torch.full((B, M, d), float("nan"), dtype=tdtype(dtype), device="cuda")
+    fv.fvar_cache_fill(blk.ctx, y_keep, keep, drop, B, M, r, to_dev(Cm, dtype), y)
+    torch.cuda.synchronize()
+    ow = oracle.BlockWeights(**w)
+    for b in range(B):
+        Kc = np.zeros((Lp + r, H, d // H), np.float32); Vc = np.zeros_like(Kc)
+        Kc[:Lp], Vc[:Lp] = Kp[b], Vp[b]
+        ref = rp_path.rp_step(x[b], Q[0], Cm[b], ow, H, Kc, Vc, Lp, bf16=dtype == "bf16")
+        assert rel_err(to_np(f_r[b]), ref["f_r"]) <= TOL[dtype]
+        assert np.array_equal(keep[b].cpu().numpy(), ref["idx_keep"])
+        assert np.array_equal(drop[b].cpu().numpy(), ref["idx_drop"])
+        assert rel_err(to_np(y_keep[b]), ref["y_keep"]) <= TOL[dtype], rel_err(to_np(y_keep[b]), ref["y_keep"])
+        assert rel_err(to_np(blk.K[b, Lp:]), Kc[Lp:]) <= TOL[dtype]
+        assert rel_err(to_np(blk.V[b, Lp:]), Vc[Lp:]) <= TOL[dtype]
+        yg = to_np(y[b])
+        assert np.array_equal(yg[ref["idx_drop"]], Cm[b][ref["idx_drop"]])
+        assert np.array_equal(yg[ref["idx_keep"]], to_np(y_keep[b]))
+
+
+def test_rp_project_depth30_launch_shape_sampled():
+    # the shape the benchmark times (batch 8, scale 32, 410 of 1024 rows): sampled output rows
+    W = wl.WORKLOADS["var_d30_512_bf16"]
+    B, M, d = W.batch, W.tokens(32), W.hidden
+    r = W.keep(32)
+    x = wl.activations_lowrank(B, M, d, seed=1002, bf16=True)
+    Q = _q(B, M, r, 4002, "bf16", False)
+    ctx = _ctx(d, "bf16", H=W.heads)
+    out = torch.empty((B, r, d), dtype=torch.bfloat16, device="cuda")
+    fv.fvar_rp_project(ctx, _qt_dev(Q, "bf16"), False, to_dev(x, "bf16"), B, M, r, out)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    for b in (0, 3, 7):
+        rows = np.concatenate([[0, r - 1, 127, 128, 383, 384], rng.integers(0, r, 10)])
+        ref = Q[0][:, rows].astype(np.float64).T @ x[b].astype(np.float64)
+        assert rel_err(to_np(out[b])[rows], factors.round_bf16(ref)) <= TOL["bf16"]
