@@ -79,6 +79,63 @@ class Chain:
             x = y
         return x
 
+    def rp_state(self, side):
+        """Extra device state of the random-projection input variant and of the factor
+        construction: Q^T [k,M] and [r,M] with N(0,1/rows) entries, and a cached counterpart
+        feature C (same recipe as the block input, other seed)."""
+        import workloads as wl
+        s, W, torch = self.scale[side], self.W, self.torch
+        if "Qt" not in s:
+            g = torch.Generator(device="cuda").manual_seed(4100 + side)
+            dt = s["x0"].dtype
+            for name, rows in (("Qt", s["k"]), ("Qt_r", W.rank)):
+                s[name] = (torch.randn((rows, s["M"]), generator=g, device="cuda") /
+                           rows ** 0.5).to(dt)
+            s["C"] = wl.device_workload(W, side, seed=5000)[0]
+            s["f_r"] = torch.empty_like(s["y_keep"])
+            s["Wf"], s["Gf"] = torch.empty_like(s["Wc"][0]), torch.empty_like(s["Gc"][0])
+        return s
+
+    def rp_scale(self, side):
+        """The fidelity stage as the paper's algorithm prints it: the block runs on the k rows
+        Q^T x, its outputs go to the selected positions and the raw cached rows to the others."""
+        fv, W, s = self.fv, self.W, self.rp_state(side)
+        B, M, k = W.batch, s["M"], s["k"]
+        x = s["x0"]
+        for i, (w, K, V) in enumerate(self.blocks):
+            y = s["bufs"][i & 1]
+            fv.fvar_score_select(self.ctx, x, B, M, k, s["keep"], s["drop"], ws=self.sel_ws)
+            fv.fvar_rp_project(self.ctx, s["Qt"], False, x, B, M, k, s["f_r"])
+            fv.fvar_block_forward_dense(self.ctx, w, s["f_r"], B, k, K, V, self.cap, s["Lp"],
+                                        s["y_keep"], self.ws)
+            fv.fvar_cache_fill(self.ctx, s["y_keep"], s["keep"], s["drop"], B, M, k, s["C"], y)
+            x = y
+        return x
+
+    def factors(self, side):
+        """W_c, G_c of the cached counterpart feature of one block at one scale."""
+        fv, W, s = self.fv, self.W, self.rp_state(side)
+        B, M, r = W.batch, s["M"], W.rank
+        if "fws" not in s:
+            s["fws"] = self.torch.empty(fv.fvar_factors_workspace_bytes(self.ctx, B, M, r),
+                                        dtype=self.torch.uint8, device="cuda")
+        fv.fvar_cache_factors(self.ctx, s["C"], s["Qt_r"], False, B, M, r, 0.0, s["Wf"], s["Gf"],
+                              s["fws"])
+
+    def factors_all_blocks(self, side):
+        """The same construction for the cached features of all blocks of the scale in one call
+        (they are all known once the previous scale is finished): batch = blocks x B."""
+        fv, W, s = self.fv, self.W, self.rp_state(side)
+        n, M, r, torch = W.batch * W.blocks, s["M"], W.rank, self.torch
+        if "C_all" not in s:
+            s["C_all"] = s["C"].repeat(W.blocks, 1, 1).contiguous()
+            s["W_all"] = torch.empty((n, M, r), dtype=s["C"].dtype, device="cuda")
+            s["G_all"] = torch.empty((n, r, W.hidden), dtype=s["C"].dtype, device="cuda")
+            s["fws_all"] = torch.empty(fv.fvar_factors_workspace_bytes(self.ctx, n, M, r),
+                                       dtype=torch.uint8, device="cuda")
+        fv.fvar_cache_factors(self.ctx, s["C_all"], s["Qt_r"], False, n, M, r, 0.0, s["W_all"],
+                              s["G_all"], s["fws_all"])
+
     def step(self, dense=False, events=None):
         for side in self.W.late_scales:
             if events is not None:
@@ -112,7 +169,81 @@ def kernel_work(W, side):
     out["gather_ln1"] = ("byte", B * k * (3.0 * d * es + 4))
     out["ln2"] = ("byte", B * k * d * (4.0 + es))       # reads the fp32 residual stream
     out["fill"] = ("byte", B * (M * d * es + k * d * es + (M - k) * r * es + r * d * es))
+    # random-projection input variant and factor construction
+    out["rp_project"] = ("flop", 2.0 * B * k * M * d)
+    out["cache_fill"] = ("byte", 2.0 * B * M * d * es)
+    out["factor_project"] = ("flop", 2.0 * B * r * M * d)
+    out["factor_t"] = ("byte", B * (M * d * es + r * d * es + M * r * 4.0))
+    out["factor_gram"] = ("flop", 2.0 * B * r * r * d)
+    out["factor_inverse"] = ("flop", B * (r ** 3) * (1.0 / 3 + 1.0 / 3 + 2.0 / 3))
+    out["factor_w"] = ("flop", 2.0 * B * M * r * r)
     return out
+
+
+def rates(prof, work):
+    """{label: avg_us and achieved rate} from a profile read and the per-launch work table."""
+    rep = {}
+    for lab, (launches, total_ms) in prof.items():
+        kind, amount = work[lab]
+        rate = amount * launches / (total_ms * 1e-3)
+        rep[lab] = {"avg_us": round(total_ms * 1e3 / launches, 2)}
+        rep[lab]["TFLOP/s" if kind == "flop" else "GB/s"] = round(rate / (1e12 if kind == "flop" else 1e9), 2)
+    return rep
+
+
+def variants(chain, W, fv, torch, steps):
+    """The random-projection input variant of the same chain, and the construction of the cache
+    factors, measured the same way (not part of `value`)."""
+    tokens = W.batch * sum(W.tokens(s) for s in W.late_scales)
+    for side in W.late_scales:
+        chain.rp_scale(side)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for side in W.late_scales:
+            chain.rp_scale(side)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    fv.fvar_profile_enable(chain.ctx, True)
+    rp_k, fac = {}, {}
+    for side in W.late_scales:
+        chain.rp_scale(side)
+        torch.cuda.synchronize()
+        prof = fv.fvar_profile_read(chain.ctx)
+        rp_k[str(side)] = rates({l: v for l, v in prof.items() if l in ("rp_project", "cache_fill")},
+                                kernel_work(W, side))
+        for _ in range(5):
+            chain.factors(side)
+        torch.cuda.synchronize()
+        prof = fv.fvar_profile_read(chain.ctx)
+        fac[str(side)] = {"kernels": rates(prof, kernel_work(W, side)),
+                          "us_per_call_kernels": round(sum(v[1] for v in prof.values()) * 1e3 / 5, 1)}
+    fv.fvar_profile_enable(chain.ctx, False)
+    for side in W.late_scales:                       # wall time of the factor call, launch gaps included
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            chain.factors(side)
+        torch.cuda.synchronize()
+        fac[str(side)]["us_per_call"] = round((time.perf_counter() - t0) * 1e6 / 20, 1)
+        chain.factors_all_blocks(side)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            chain.factors_all_blocks(side)
+        torch.cuda.synchronize()
+        fac[str(side)]["us_per_block_when_all_blocks_batched"] = round(
+            (time.perf_counter() - t0) * 1e6 / 5 / W.blocks, 1)
+        fv.fvar_profile_enable(chain.ctx, True)
+        chain.factors_all_blocks(side)
+        torch.cuda.synchronize()
+        fac[str(side)]["batched_kernels_us_per_block"] = {
+            l: round(v[1] * 1e3 / W.blocks, 2) for l, v in fv.fvar_profile_read(chain.ctx).items()}
+        fv.fvar_profile_enable(chain.ctx, False)
+        for k in ("C_all", "W_all", "G_all", "fws_all"):
+            chain.scale[side].pop(k)
+    return {"rp_input_path": {"ms_per_step": ms, "tokens_per_s": tokens / (ms * 1e-3), "kernels": rp_k},
+            "cache_factors": fac}
 
 
 def cpu_baseline(W):
@@ -151,6 +282,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the random-projection input variant and the factor construction")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB device copy (reference for scaling HBM counters)")
     args = ap.parse_args()
@@ -259,6 +392,8 @@ def main():
         "roofline": roofline,
         "kernels": report,
     }
+    if not args.no_variants:
+        out["variants"] = variants(chain, W, fv, torch, max(2, args.steps // 3))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(W)
     print(json.dumps(out))

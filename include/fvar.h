@@ -192,9 +192,9 @@ fvar_status fvar_cache_fill(fvar_ctx *ctx, fvar_stream stream, const void *y_kee
  *   w_c[b] = store(argmin_W || W g_c[b] - cache[b] ||_F)             [M,r]
  *          = store((cache g_c^T)(g_c g_c^T + ridge*trace/r*I)^{-1})
  * store() rounds to the context's element type; the least-squares problem is posed against the
- * stored g_c.  Gram matrix, Cholesky factorisation and the final product run in fp64.  A Gram
- * matrix that is not positive definite (r above the rank of the cache with ridge == 0) gives
- * non-finite w_c; pass a small ridge (e.g. 1e-10) then.  qt, q_per_sample as in fvar_rp_project.
+ * stored g_c.  Gram matrix, its inverse (elimination without pivoting: the matrix is symmetric
+ * positive definite) and the final product run in fp64.  A singular Gram matrix (r above the
+ * rank of the cache with ridge == 0) gives non-finite w_c; pass a small ridge (e.g. 1e-10) then.  qt, q_per_sample as in fvar_rp_project.
  * 1 <= r <= min(M,128), r a multiple of 8 for bf16 (of 4 for fp32); M as in fvar_rp_project.
  * ws: at least fvar_factors_workspace_bytes(ctx,B,M,r). */
 size_t fvar_factors_workspace_bytes(const fvar_ctx *ctx, int32_t B, int32_t M, int32_t r);

@@ -396,7 +396,9 @@ fvar_status fvar_cache_fill(fvar_ctx *c, fvar_stream stream, const void *y_keep,
 size_t fvar_factors_workspace_bytes(const fvar_ctx *c, int32_t B, int32_t M, int32_t r)
 {
     if (!c || B < 1 || M < 1 || r < 1) return 0;
-    return align256((size_t)B * M * r * sizeof(float)) + 2 * align256((size_t)B * r * r * sizeof(double));
+    const size_t rr = (size_t)B * r * r * sizeof(double);
+    return align256((size_t)B * M * r * sizeof(float) * fvar::factor_t_parts(dtype(c), B, M)) +
+           align256(rr * fvar::gram_parts(dtype(c))) + align256(rr);
 }
 
 fvar_status fvar_cache_factors(fvar_ctx *c, fvar_stream stream, const void *cache, const void *qt,
@@ -425,9 +427,9 @@ fvar_status fvar_cache_factors(fvar_ctx *c, fvar_stream stream, const void *cach
                     ws_bytes);
     char *p = static_cast<char *>(ws);
     float *T = reinterpret_cast<float *>(p);
-    p += align256((size_t)B * M * r * sizeof(float));
+    p += align256((size_t)B * M * r * sizeof(float) * fvar::factor_t_parts(dtype(c), B, M));
     double *S = reinterpret_cast<double *>(p);
-    p += align256((size_t)B * r * r * sizeof(double));
+    p += align256((size_t)B * r * r * sizeof(double) * fvar::gram_parts(dtype(c)));
     double *Sinv = reinterpret_cast<double *>(p);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const DType dt = dtype(c);
@@ -437,7 +439,7 @@ fvar_status fvar_cache_factors(fvar_ctx *c, fvar_stream stream, const void *cach
     });
     timed(c, st, "factor_t", [&] { fvar::launch_factor_t(dt, cache, g_c, B, M, r, d, T, st); });
     timed(c, st, "factor_gram", [&] { fvar::launch_factor_gram(dt, g_c, B, r, d, S, st); });
-    timed(c, st, "factor_inverse", [&] { fvar::launch_factor_inverse(S, B, r, ridge, Sinv, st); });
+    timed(c, st, "factor_inverse", [&] { fvar::launch_factor_inverse(S, fvar::gram_parts(dt), B, r, ridge, Sinv, st); });
     timed(c, st, "factor_w", [&] { fvar::launch_factor_w(dt, T, Sinv, B, M, r, w_c, st); });
     return launch_status(c, who);
 }

@@ -153,12 +153,15 @@ void launch_cache_fill(DType dt, const void *y_keep, const int32_t *idx_keep, co
 void launch_rp_project(DType dt, const void *qt, size_t q_stride, const void *x, int B, int M,
                        int rows, int d, void *out, hipStream_t st);
 
-// restoration matrix W_c = (C G_c^T)(G_c G_c^T)^{-1} in four steps; T:[B,M,r] fp32,
-// S, Sinv:[B,r,r] fp64 are scratch.  r <= 128.
+// restoration matrix W_c = (C G_c^T)(G_c G_c^T)^{-1} in four steps; T:[factor_t_parts (1 or 2),B,M,r] fp32,
+// S:[B,gram_parts(dt),r,r] and Sinv:[B,r,r] fp64 are scratch.  r <= 128.
+int factor_t_parts(DType dt, int B, int M);
 void launch_factor_t(DType dt, const void *cache, const void *g_c, int B, int M, int r, int d, float *T,
                      hipStream_t st);
 void launch_factor_gram(DType dt, const void *g_c, int B, int r, int d, double *S, hipStream_t st);
-void launch_factor_inverse(const double *S, int B, int r, double ridge, double *Sinv, hipStream_t st);
+int gram_parts(DType dt);
+void launch_factor_inverse(const double *S, int parts, int B, int r, double ridge, double *Sinv,
+                           hipStream_t st);
 void launch_factor_w(DType dt, const float *T, const double *Sinv, int B, int M, int r, void *w_c,
                      hipStream_t st);
 

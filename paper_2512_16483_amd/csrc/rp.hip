@@ -11,21 +11,37 @@
 
 namespace fvar {
 
-constexpr int kRpBM = 128, kRpBN = 128, kRpBK = 64;
-constexpr int kRpPitch = kRpBK + 8;          // X^T row pitch (elements): 9 chunks of 16 bytes
+constexpr int kRpBN = 128, kRpBK = 64;
+constexpr int kRpPitch = kRpBK;              // X^T row = 8 chunks of 16 bytes, swizzled
 constexpr int kRpOutPitch = kRpBN + 8;       // output staging pitch
 
+// Chunk swizzle of the X^T tile (rows = columns of X, 8 chunks of 8 tokens).  MFMA operand reads
+// fetch 16 consecutive rows at one logical chunk: (row/2)%8 spreads those over all 64 banks, and
+// the other terms are constant inside an aligned group of 16 rows.  The transposing stores write
+// 8-byte halves to rows 8 apart; the row/16 terms send those to different chunks.
+__device__ __forceinline__ int xt_swz(int row)
+{
+    return ((row >> 1) & 7) ^ (((row >> 4) & 1) << 2) ^ ((row >> 5) & 3);
+}
+
+// BM = output rows per workgroup (128, or 64 when few rows are asked for); the four wavefronts
+// form a 2 x 2 grid of (BM/2) x 64 tiles.
+template <int BM>
 __global__ __launch_bounds__(256) void rp_project_bf16_kernel(const uint16_t *__restrict__ qt,
                                                               size_t q_stride,
                                                               const uint16_t *__restrict__ x, int M,
                                                               int rows, int d,
                                                               uint16_t *__restrict__ out)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kRpBN * kRpPitch];
+    // two X^T buffers during the main loop, the BM x kRpOutPitch output staging afterwards
+    constexpr int kLdsElems = 2 * kRpBN * kRpPitch > BM * kRpOutPitch ? 2 * kRpBN * kRpPitch
+                                                                      : BM * kRpOutPitch;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[kLdsElems];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rl = lane & 31, g = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
-    const int col0 = blockIdx.x * kRpBN, row0 = blockIdx.y * kRpBM, b = blockIdx.z;
+    constexpr int MI = BM / 64;                // 32-row MFMA tiles per wavefront
+    const int col0 = blockIdx.x * kRpBN, row0 = blockIdx.y * BM, b = blockIdx.z;
     const uint16_t *Q = qt + (size_t)b * q_stride;
     const uint16_t *X = x + (size_t)b * M * d;
     uint16_t *O = out + (size_t)b * rows * d;
@@ -54,18 +70,25 @@ __global__ __launch_bounds__(256) void rp_project_bf16_kernel(const uint16_t *__
             lo.y = __builtin_amdgcn_perm(w3[m], w2[m], 0x05040100u);
             hi.x = __builtin_amdgcn_perm(w1[m], w0[m], 0x07060302u);
             hi.y = __builtin_amdgcn_perm(w3[m], w2[m], 0x07060302u);
-            *reinterpret_cast<uint2 *>(buf + (cb * 8 + 2 * m) * kRpPitch + tb * 4) = lo;
-            *reinterpret_cast<uint2 *>(buf + (cb * 8 + 2 * m + 1) * kRpPitch + tb * 4) = hi;
+            // threads of odd column blocks store the odd row first, so that one store instruction
+            // touches rows of both parities (both halves of the banks)
+            const int r0 = cb * 8 + 2 * m, r1 = r0 + 1;
+            const int ra = (cb & 1) ? r1 : r0, rb = (cb & 1) ? r0 : r1;
+            const int chunk = tb >> 1, sub = (tb & 1) * 4;
+            *reinterpret_cast<uint2 *>(buf + ra * kRpPitch + ((chunk ^ xt_swz(ra)) << 3) + sub) =
+                (cb & 1) ? hi : lo;
+            *reinterpret_cast<uint2 *>(buf + rb * kRpPitch + ((chunk ^ xt_swz(rb)) << 3) + sub) =
+                (cb & 1) ? lo : hi;
         }
     };
     // A operand rows of this lane (clamped: rows past the end are computed and dropped)
-    const uint16_t *qrow[2];
+    const uint16_t *qrow[MI];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-        qrow[i] = Q + (size_t)min(row0 + wm * 64 + i * 32 + rl, rows - 1) * M;
-    auto load_a = [&](int k0, uint4 (&a)[2][4]) {
+    for (int i = 0; i < MI; ++i)
+        qrow[i] = Q + (size_t)min(row0 + wm * (BM / 2) + i * 32 + rl, rows - 1) * M;
+    auto load_a = [&](int k0, uint4 (&a)[MI][4]) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const int t = k0 + 16 * s + 8 * g;
@@ -73,14 +96,14 @@ __global__ __launch_bounds__(256) void rp_project_bf16_kernel(const uint16_t *__
             }
     };
 
-    floatx16_t acc[2][2];
+    floatx16_t acc[MI][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = floatx16_t{0};
 
     const int nchunks = (M + kRpBK - 1) / kRpBK;
-    uint4 xv[4], av[2][4];
+    uint4 xv[4], av[MI][4];
     load_x(0, xv);
     load_a(0, av);
     store_xt(lds, xv);
@@ -89,7 +112,7 @@ __global__ __launch_bounds__(256) void rp_project_bf16_kernel(const uint16_t *__
         uint16_t *cur = lds + (c & 1) * (kRpBN * kRpPitch);
         uint16_t *nxt = lds + ((c + 1) & 1) * (kRpBN * kRpPitch);
         const bool more = c + 1 < nchunks;
-        uint4 an[2][4];
+        uint4 an[MI][4];
         if (more) {
             load_x((c + 1) * kRpBK, xv);
             load_a((c + 1) * kRpBK, an);
@@ -98,11 +121,13 @@ __global__ __launch_bounds__(256) void rp_project_bf16_kernel(const uint16_t *__
         for (int s = 0; s < 4; ++s) {
             bf16x8_t bf[2];
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                bf[j] = *reinterpret_cast<const bf16x8_t *>(cur + (wn * 64 + j * 32 + rl) * kRpPitch +
-                                                            16 * s + 8 * g);
+            for (int j = 0; j < 2; ++j) {
+                const int row = wn * 64 + j * 32 + rl;
+                bf[j] = *reinterpret_cast<const bf16x8_t *>(cur + row * kRpPitch +
+                                                            (((2 * s + g) ^ xt_swz(row)) << 3));
+            }
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
@@ -111,7 +136,7 @@ __global__ __launch_bounds__(256) void rp_project_bf16_kernel(const uint16_t *__
         if (more) {
             store_xt(nxt, xv);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int s = 0; s < 4; ++s) av[i][s] = an[i][s];
         }
@@ -120,10 +145,10 @@ __global__ __launch_bounds__(256) void rp_project_bf16_kernel(const uint16_t *__
 
     // accumulators -> bf16 row-major in LDS (neighbouring lanes swap one value per row pair so a
     // lane owns two adjacent columns), then 16-byte row chunks to global memory
-    uint16_t *stage = lds;                    // 128 x kRpOutPitch elements fit the two X^T buffers
+    uint16_t *stage = lds;
     const int odd = lane & 1;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int lcol = wn * 64 + j * 32 + rl - odd;
@@ -131,7 +156,7 @@ __global__ __launch_bounds__(256) void rp_project_bf16_kernel(const uint16_t *__
             for (int e = 0; e < 16; e += 2) {
                 const float v0 = acc[i][j][e], v1 = acc[i][j][e + 1];
                 const float recv = __shfl_xor(odd ? v0 : v1, 1);
-                const int lrow = wm * 64 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3) + odd;
+                const int lrow = wm * (BM / 2) + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3) + odd;
                 *reinterpret_cast<uint32_t *>(stage + lrow * kRpOutPitch + lcol) =
                     odd ? pack_bf16x2(recv, v1) : pack_bf16x2(v0, recv);
             }
@@ -139,7 +164,7 @@ __global__ __launch_bounds__(256) void rp_project_bf16_kernel(const uint16_t *__
     __syncthreads();
     const int c8 = (tid & 15) * 8;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
+    for (int it = 0; it < BM / 16; ++it) {
         const int lrow = it * 16 + (tid >> 4), rr = row0 + lrow;
         if (rr < rows && col0 + c8 < d)
             *reinterpret_cast<uint4 *>(O + (size_t)rr * d + col0 + c8) =
@@ -173,9 +198,15 @@ void launch_rp_project(DType dt, const void *qt, size_t q_stride, const void *x,
                        int rows, int d, void *out, hipStream_t st)
 {
     if (dt == DType::BF16) {
-        dim3 grid((d + kRpBN - 1) / kRpBN, (rows + kRpBM - 1) / kRpBM, B);
-        launch(rp_project_bf16_kernel, grid, dim3(256), 0, st, (const uint16_t *)qt, q_stride,
-               (const uint16_t *)x, M, rows, d, (uint16_t *)out);
+        if (rows <= 64 || (rows > 128 && rows <= 192)) {
+            dim3 grid((d + kRpBN - 1) / kRpBN, (rows + 63) / 64, B);
+            launch(rp_project_bf16_kernel<64>, grid, dim3(256), 0, st, (const uint16_t *)qt, q_stride,
+                   (const uint16_t *)x, M, rows, d, (uint16_t *)out);
+        } else {
+            dim3 grid((d + kRpBN - 1) / kRpBN, (rows + 127) / 128, B);
+            launch(rp_project_bf16_kernel<128>, grid, dim3(256), 0, st, (const uint16_t *)qt, q_stride,
+                   (const uint16_t *)x, M, rows, d, (uint16_t *)out);
+        }
     } else {
         dim3 grid((d + 255) / 256, (rows + 7) / 8, B);
         launch(rp_project_f32_kernel, grid, dim3(256), 0, st, (const float *)qt, q_stride,

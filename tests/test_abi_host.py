@@ -112,7 +112,7 @@ def test_entry_points_reject_bad_arguments_without_launching():
     assert lib.fvar_cache_fill(h, None, None, fake, fake, 1, 10, 5, fake, fake) == fv.FVAR_ERR_INVALID_ARG
     # factors: rank limits, ridge sign, workspace
     need = fv.fvar_factors_workspace_bytes(c, 2, 64, 16)
-    assert need == 2 * 64 * 16 * 4 + 2 * (2 * 16 * 16 * 8)
+    assert need == 2 * 2 * 64 * 16 * 4 + (8 + 1) * (2 * 16 * 16 * 8)     # 2 slices of T, 8 partial Gram matrices, inverse
     assert lib.fvar_cache_factors(h, None, fake, fake, 0, 2, 64, 136, 0.0, fake, fake, fake, 1 << 30) == fv.FVAR_ERR_INVALID_ARG
     assert lib.fvar_cache_factors(h, None, fake, fake, 0, 2, 256, 136, 0.0, fake, fake, fake, 1 << 30) == fv.FVAR_ERR_UNSUPPORTED
     assert lib.fvar_cache_factors(h, None, fake, fake, 0, 2, 64, 12, 0.0, fake, fake, fake, 1 << 30) == fv.FVAR_ERR_UNSUPPORTED
