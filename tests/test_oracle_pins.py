@@ -498,3 +498,29 @@ def test_stored_factors_solve_against_the_stored_g():
     # solving against the unrounded product instead leaves a visible normal-equation residual
     Wwrong = factors.restoration_matrix(factors.project(Q, Cm), Cm)
     assert np.abs((Cm - Wwrong @ G64) @ G64.T).max() > 1e-6 * scale
+
+
+# ----------------------------------------------------------------------------- cache up-sampling
+def test_upsample_matches_library_bilinear_and_is_linear_on_tokens():
+    from oracle import upsample
+    rng = np.random.default_rng(8)
+    for (hs, ws, hd, wd) in [(3, 3, 4, 4), (24, 24, 32, 32), (5, 7, 8, 9), (4, 4, 4, 4), (6, 6, 3, 3), (1, 1, 5, 5)]:
+        c = 6
+        src = rng.standard_normal((hs * ws, c))
+        got = upsample.upsample_tokens(src, hs, ws, hd, wd)
+        t = torch.from_numpy(src.reshape(hs, ws, c)).permute(2, 0, 1)[None]
+        ref = torch.nn.functional.interpolate(t, size=(hd, wd), mode="bilinear", align_corners=False)
+        ref = ref[0].permute(1, 2, 0).reshape(hd * wd, c).numpy()
+        assert np.abs(got - ref).max() < 1e-12, (hs, ws, hd, wd)
+    # hand case: 2 -> 4 along one axis gives weights (1, 3/4|1/4, 1/4|3/4, 1)
+    one = upsample.upsample_tokens(np.array([[0.0], [4.0]]), 2, 1, 4, 1)[:, 0]
+    assert one.tolist() == [0.0, 1.0, 3.0, 4.0]
+    # same size is the identity; a constant map stays constant
+    a = rng.standard_normal((20, 3))
+    assert np.array_equal(upsample.upsample_tokens(a, 4, 5, 4, 5), a)
+    assert np.allclose(upsample.upsample_tokens(np.full((9, 2), 2.5), 3, 3, 7, 5), 2.5, rtol=0, atol=1e-15)
+    # linear on the token axis: Up(W G) = Up(W) G  (the thin-factor form of Eq. "upcache")
+    Wm = rng.standard_normal((6 * 6, 4)); G = rng.standard_normal((4, 10))
+    lhs = upsample.upsample_tokens(Wm @ G, 6, 6, 8, 8)
+    rhs = upsample.upsample_tokens(Wm, 6, 6, 8, 8) @ G
+    assert np.abs(lhs - rhs).max() < 1e-12
