@@ -18,6 +18,9 @@
  *     fvar_block_forward_dense   f_r (as r tokens)   -> y_keep[B,r,d]   (appends r K/V rows)
  *     fvar_cache_fill            y_keep, idx, cache  -> y[B,M,d]
  *
+ * fvar_upsample_tokens brings a cached token map (or the thin factor W_c of its
+ * rank-r form) from the previous scale's grid to the current one.
+ *
  * Conventions common to every call
  *  - Every tensor pointer is DEVICE memory owned by the caller, row-major,
  *    contiguous, 16-byte aligned, of element type `fvar_config.dtype`
@@ -201,6 +204,18 @@ size_t fvar_factors_workspace_bytes(const fvar_ctx *ctx, int32_t B, int32_t M, i
 fvar_status fvar_cache_factors(fvar_ctx *ctx, fvar_stream stream, const void *cache, const void *qt,
                                int32_t q_per_sample, int32_t B, int32_t M, int32_t r, double ridge,
                                void *w_c, void *g_c, void *ws, size_t ws_bytes);
+
+/* Up-sampling of a cached token map to the token grid of the next scale (paper, Eq. "upcache":
+ * F^{o,cache}_{k-1} = Up(F^o_{k-1})).  The paper does not name the interpolation; this is
+ * bilinear interpolation with half-pixel centres and clamped edges, applied to the token axis:
+ *   src:[B][hs*ws][c] (row-major hs x ws grid)  ->  dst:[B][hd*wd][c]
+ * It is linear in the tokens, so a cache kept as W_c G_c is up-sampled by passing W_c (c = r):
+ * Up(W_c G_c) = Up(W_c) G_c.  c a multiple of 8 for bf16 (of 4 for fp32); any grid sizes >= 1
+ * (hd < hs down-samples without anti-aliasing).  fp32 arithmetic.  No workspace; src and dst
+ * must not overlap. */
+fvar_status fvar_upsample_tokens(fvar_ctx *ctx, fvar_stream stream, const void *src, int32_t B,
+                                 int32_t hs, int32_t ws, int32_t c, int32_t hd, int32_t wd,
+                                 void *dst);
 
 /* Per-kernel timing (hipEvent pairs around every launch while enabled).  Off by default and
  * outside any throughput measurement.  fvar_profile_read synchronises the recorded events,

@@ -20,7 +20,8 @@ EXPORTS = (
     "fvar_scale_tokens", "fvar_scale_prev_len", "fvar_select_workspace_bytes",
     "fvar_block_workspace_bytes", "fvar_score_select", "fvar_block_forward_dense",
     "fvar_block_forward_pruned", "fvar_lowrank_fill", "fvar_rp_project", "fvar_cache_fill",
-    "fvar_factors_workspace_bytes", "fvar_cache_factors", "fvar_profile_enable",
+    "fvar_factors_workspace_bytes", "fvar_cache_factors", "fvar_upsample_tokens",
+    "fvar_profile_enable",
     "fvar_profile_read",
 )
 
@@ -101,6 +102,8 @@ def load_library() -> C.CDLL:
     lib.fvar_factors_workspace_bytes.restype = sz
     lib.fvar_cache_factors.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, C.c_double, vp, vp, vp, sz]
     lib.fvar_cache_factors.restype = C.c_int
+    lib.fvar_upsample_tokens.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
+    lib.fvar_upsample_tokens.restype = C.c_int
     lib.fvar_profile_enable.argtypes = [vp, i32]
     lib.fvar_profile_enable.restype = C.c_int
     lib.fvar_profile_read.argtypes = [vp, C.POINTER(_ProfileEntry), i32]
@@ -252,6 +255,12 @@ def fvar_cache_factors(ctx: Context, cache, qt, q_per_sample: bool, B: int, M: i
     ctx.check(ctx.lib.fvar_cache_factors(ctx.handle, _stream(stream), _ptr(cache), _ptr(qt),
                                          1 if q_per_sample else 0, B, M, r, float(ridge), _ptr(w_c),
                                          _ptr(g_c), _ptr(ws), _nbytes(ws)))
+
+
+def fvar_upsample_tokens(ctx: Context, src, B: int, hs: int, ws: int, c: int, hd: int, wd: int, dst,
+                         stream=None) -> None:
+    ctx.check(ctx.lib.fvar_upsample_tokens(ctx.handle, _stream(stream), _ptr(src), B, hs, ws, c, hd,
+                                           wd, _ptr(dst)))
 
 
 def fvar_profile_enable(ctx: Context, on: bool) -> None:

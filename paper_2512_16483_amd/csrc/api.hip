@@ -444,6 +444,31 @@ fvar_status fvar_cache_factors(fvar_ctx *c, fvar_stream stream, const void *cach
     return launch_status(c, who);
 }
 
+fvar_status fvar_upsample_tokens(fvar_ctx *c, fvar_stream stream, const void *src, int32_t B,
+                                 int32_t hs, int32_t ws, int32_t ch, int32_t hd, int32_t wd,
+                                 void *dst)
+{
+    if (!c) return FVAR_ERR_INVALID_ARG;
+    const char *who = "fvar_upsample_tokens";
+    if (B < 1 || hs < 1 || ws < 1 || hd < 1 || wd < 1 || ch < 1)
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: sizes must be >= 1", who);
+    if (!src || !dst) return fail(c, FVAR_ERR_INVALID_ARG, "%s: null argument", who);
+    if (!aligned16(src) || !aligned16(dst))
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: pointer not 16-byte aligned", who);
+    const int mult = c->cfg.dtype == FVAR_BF16 ? 8 : 4;
+    if (ch % mult)
+        return fail(c, FVAR_ERR_UNSUPPORTED, "%s: channel count %d must be a multiple of %d", who, ch,
+                    mult);
+    if ((int64_t)hs * ws > (1 << 24) || (int64_t)hd * wd > (1 << 24) ||
+        (int64_t)B * hd * wd * (ch / mult) > ((int64_t)1 << 38))
+        return fail(c, FVAR_ERR_UNSUPPORTED, "%s: grid too large", who);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    timed(c, st, "upsample", [&] {
+        fvar::launch_upsample(dtype(c), src, B, hs, ws, hd, wd, ch, dst, st);
+    });
+    return launch_status(c, who);
+}
+
 fvar_status fvar_profile_enable(fvar_ctx *c, int32_t on)
 {
     if (!c) return FVAR_ERR_INVALID_ARG;

@@ -153,6 +153,11 @@ void launch_cache_fill(DType dt, const void *y_keep, const int32_t *idx_keep, co
 void launch_rp_project(DType dt, const void *qt, size_t q_stride, const void *x, int B, int M,
                        int rows, int d, void *out, hipStream_t st);
 
+// bilinear up-sampling of token maps src:[B,hs*ws,c] -> dst:[B,hd*wd,c]; c a multiple of the
+// 16-byte chunk
+void launch_upsample(DType dt, const void *src, int B, int hs, int ws, int hd, int wd, int c,
+                     void *dst, hipStream_t st);
+
 // restoration matrix W_c = (C G_c^T)(G_c G_c^T)^{-1} in four steps; T:[factor_t_parts (1 or 2),B,M,r] fp32,
 // S:[B,gram_parts(dt),r,r] and Sinv:[B,r,r] fp64 are scratch.  r <= 128.
 int factor_t_parts(DType dt, int B, int M);

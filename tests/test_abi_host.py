@@ -110,6 +110,10 @@ def test_entry_points_reject_bad_arguments_without_launching():
     assert lib.fvar_cache_fill(h, None, fake, fake, None, 1, 10, 5, fake, fake) == fv.FVAR_ERR_INVALID_ARG
     assert lib.fvar_cache_fill(h, None, fake, fake, fake, 1, 10, 5, None, fake) == fv.FVAR_ERR_INVALID_ARG
     assert lib.fvar_cache_fill(h, None, None, fake, fake, 1, 10, 5, fake, fake) == fv.FVAR_ERR_INVALID_ARG
+    # up-sampling: sizes >= 1, channels a multiple of the 16-byte chunk
+    assert lib.fvar_upsample_tokens(h, None, fake, 1, 0, 4, 8, 8, 8, fake) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_upsample_tokens(h, None, None, 1, 4, 4, 8, 8, 8, fake) == fv.FVAR_ERR_INVALID_ARG
+    assert lib.fvar_upsample_tokens(h, None, fake, 1, 4, 4, 12, 8, 8, fake) == fv.FVAR_ERR_UNSUPPORTED
     # factors: rank limits, ridge sign, workspace
     need = fv.fvar_factors_workspace_bytes(c, 2, 64, 16)
     assert need == 2 * 2 * 64 * 16 * 4 + (8 + 1) * (2 * 16 * 16 * 8)     # 2 slices of T, 8 partial Gram matrices, inverse

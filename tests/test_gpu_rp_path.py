@@ -224,3 +224,57 @@ def test_rp_project_depth30_launch_shape_sampled():
         rows = np.concatenate([[0, r - 1, 127, 128, 383, 384], rng.integers(0, r, 10)])
         ref = Q[0][:, rows].astype(np.float64).T @ x[b].astype(np.float64)
         assert rel_err(to_np(out[b])[rows], factors.round_bf16(ref)) <= TOL["bf16"]
+
+
+# ----------------------------------------------------------------------------- cache up-sampling
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("B,hs,ws,hd,wd,c", [(2, 3, 3, 4, 4, 8), (1, 24, 24, 32, 32, 64), (2, 5, 7, 8, 9, 24),
+                                              (1, 4, 4, 4, 4, 16), (1, 6, 6, 3, 3, 8), (1, 1, 1, 5, 5, 8),
+                                              (1, 18, 18, 24, 24, 1920)])
+def test_upsample_tokens_parity(dtype, B, hs, ws, hd, wd, c):
+    from oracle import upsample
+    bf = dtype == "bf16"
+    src = wl.activations_iid(B, hs * ws, c, seed=110 + hs, bf16=bf)
+    ctx = _ctx(64, dtype)
+    dst = torch.full((B, hd * wd, c), float("nan"), dtype=tdtype(dtype), device="cuda")
+    fv.fvar_upsample_tokens(ctx, to_dev(src, dtype), B, hs, ws, c, hd, wd, dst)
+    torch.cuda.synchronize()
+    for b in range(B):
+        ref = upsample.upsample_tokens(src[b], hs, ws, hd, wd)
+        assert rel_err(to_np(dst[b]), ref) <= (2.0 ** -8 if bf else 1e-6)
+    if (hs, ws) == (hd, wd):
+        assert np.array_equal(to_np(dst), src)
+
+
+def test_upsampled_thin_factor_feeds_the_fill():
+    # Up(W_c G_c) = Up(W_c) G_c: up-sample the [M,r] factor on the GPU, fill with it, and compare
+    # with the oracle's fill of the oracle's up-sampled factor
+    from oracle import upsample
+    dtype, B, hs, hd, d, r = "bf16", 2, 8, 12, 256, 32
+    Ms, M, k = hs * hs, hd * hd, 58
+    Cm = wl.round_to_bf16(wl.cached_feature(B, Ms, d, 40, seed=120, noise=0.05))
+    Q = _q(B, Ms, r, 121, dtype, False)
+    ctx = _ctx(d, dtype)
+    w_s = torch.empty((B, Ms, r), dtype=torch.bfloat16, device="cuda")
+    g_c = torch.empty((B, r, d), dtype=torch.bfloat16, device="cuda")
+    ws_ = torch.empty(fv.fvar_factors_workspace_bytes(ctx, B, Ms, r), dtype=torch.uint8, device="cuda")
+    fv.fvar_cache_factors(ctx, to_dev(Cm, dtype), _qt_dev(Q, dtype), False, B, Ms, r, 0.0, w_s, g_c, ws_)
+    w_up = torch.empty((B, M, r), dtype=torch.bfloat16, device="cuda")
+    fv.fvar_upsample_tokens(ctx, w_s, B, hs, hs, r, hd, hd, w_up)
+    rng = np.random.default_rng(2)
+    keep = np.stack([np.sort(rng.choice(M, k, replace=False)) for _ in range(B)]).astype(np.int32)
+    drop = np.stack([np.setdiff1d(np.arange(M), keep[b]) for b in range(B)]).astype(np.int32)
+    yk = wl.activations_iid(B, k, d, seed=122, bf16=True)
+    y = torch.empty((B, M, d), dtype=torch.bfloat16, device="cuda")
+    fv.fvar_lowrank_fill(ctx, to_dev(yk, dtype), torch.from_numpy(keep).cuda(), torch.from_numpy(drop).cuda(),
+                         B, M, k, r, w_up, g_c, y)
+    torch.cuda.synchronize()
+    for b in range(B):
+        Wo, Go = factors.stored_factors(Cm[b], Q[0], bf16=True)
+        Wup = factors.round_bf16(upsample.upsample_tokens(Wo, hs, hs, hd, hd))
+        ref = oracle.lowrank_fill(yk[b], keep[b], drop[b], M, Wup, Go)
+        assert rel_err(to_np(y[b]), ref) <= TOL[dtype]
+        # and that restoration is the up-sampled restored cache itself; against this unrounded
+        # statement the bf16 storage of Up(W_c) and of the output both count, hence the wider bound
+        full = upsample.upsample_tokens(Wo.astype(np.float64) @ Go.astype(np.float64), hs, hs, hd, hd)
+        assert rel_err(to_np(y[b])[drop[b]], full[drop[b]]) <= 2.5 * TOL[dtype]
