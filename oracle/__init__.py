@@ -221,6 +221,25 @@ def pruned_step(x, k: int, w: BlockWeights, H: int, Kc, Vc, length: int, Wc, Gc,
     return dict(scores=s, idx_keep=keep, idx_drop=drop, y_keep=y_keep, y=Y)
 
 
+def pruned_chunk(x, k: int, ws, H: int, caches, length: int, Wc, Gc, eps=1e-6, scale=None):
+    """One block CHUNK with a single selection (the paper applies its reduction per block chunk,
+    Sec. "Experiments" / App. rank tables "block_chunks"): score and select on the chunk input,
+    gather once, run every block of the chunk on the k compact rows (each appends its k K/V rows
+    to its own cache), fill once at the end.
+
+    ws: list of BlockWeights; caches: list of (Kc, Vc) per block, modified in place.
+    Returns dict(scores, idx_keep, idx_drop, y_keep, y)."""
+    x = _f32(x)
+    M = x.shape[0]
+    s = scores(x)
+    keep, drop = topk(s, k)
+    rows = gather_rows(x, keep)
+    for w, (Kc, Vc) in zip(ws, caches):
+        rows = block_forward(rows, w, H, Kc, Vc, length, eps, scale)
+    return dict(scores=s, idx_keep=keep, idx_drop=drop, y_keep=rows,
+                y=lowrank_fill(rows, keep, drop, M, Wc, Gc))
+
+
 def keep_count(M: int, num: int, den: int) -> int:
     """k = ceil(M*num/den) in integer arithmetic, clamped to [1, M]."""
     k = -((-M * num) // den)

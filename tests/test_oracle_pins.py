@@ -524,3 +524,30 @@ def test_upsample_matches_library_bilinear_and_is_linear_on_tokens():
     lhs = upsample.upsample_tokens(Wm @ G, 6, 6, 8, 8)
     rhs = upsample.upsample_tokens(Wm, 6, 6, 8, 8) @ G
     assert np.abs(lhs - rhs).max() < 1e-12
+
+
+# ----------------------------------------------------------------------------- block chunks
+def test_pruned_chunk_of_one_block_is_the_pruned_step_and_chunks_compose():
+    x, w, H, Kp, Vp, Cm, Wc, Gc = _small_case(seed=21, noise=0.05)
+    M, d = x.shape; Lp = Kp.shape[0]; k = 7
+    Ka, Va = _cache(Kp, Vp, k)
+    ref = oracle.pruned_step(x, k, w, H, Ka, Va, Lp, Wc, Gc)
+    Kb, Vb = _cache(Kp, Vp, k)
+    one = oracle.pruned_chunk(x, k, [w], H, [(Kb, Vb)], Lp, Wc, Gc)
+    for key in ("scores", "idx_keep", "idx_drop", "y_keep", "y"):
+        assert np.array_equal(one[key], ref[key]), key
+    assert np.array_equal(Kb, Ka) and np.array_equal(Vb, Va)
+    # two blocks: the second sees the first one's compact output, checked through the independent
+    # fp64 statement of the block
+    w2 = oracle.BlockWeights(**wl.block_weights(d, w.w_fc1.shape[0], seed=77, std=0.8 / np.sqrt(d)))
+    Kp2, Vp2 = wl.kv_prefix(1, Lp, H, d // H, seed=78)
+    K1, V1 = _cache(Kp, Vp, k); K2, V2 = _cache(Kp2[0], Vp2[0], k)
+    two = oracle.pruned_chunk(x, k, [w, w2], H, [(K1, V1), (K2, V2)], Lp, Wc, Gc)
+    assert np.array_equal(two["idx_keep"], ref["idx_keep"])
+    mid, _, _ = _torch_block(x[ref["idx_keep"]], w, H, Kp, Vp)
+    out, kk2, _ = _torch_block(mid, w2, H, Kp2[0], Vp2[0])
+    assert np.abs(two["y_keep"] - out).max() < 2e-5
+    assert np.abs(K2[Lp:].reshape(k, d) - kk2).max() < 2e-5
+    assert np.array_equal(two["y"][two["idx_keep"]], two["y_keep"])
+    fill = Wc.astype(np.float64) @ Gc.astype(np.float64)
+    assert np.abs(two["y"][two["idx_drop"]] - fill[two["idx_drop"]]).max() < 1e-5
