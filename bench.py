@@ -112,6 +112,34 @@ class Chain:
             x = y
         return x
 
+    def chunked_scale(self, side, chunk=4):
+        """One selection per chunk of `chunk` blocks (the granularity the paper applies its
+        reduction at): score/select/gather at the chunk's first block, the other blocks run on
+        the compact rows, one fill at the chunk's end."""
+        fv, W, s = self.fv, self.W, self.scale[side]
+        B, M, k, r = W.batch, s["M"], s["k"], W.rank
+        if "rows2" not in s:
+            s["rows2"] = self.torch.empty_like(s["y_keep"])
+        x = s["x0"]
+        nb = len(self.blocks)
+        for c0 in range(0, nb, chunk):
+            y = s["bufs"][(c0 // chunk) & 1]
+            fv.fvar_score_select(self.ctx, x, B, M, k, s["keep"], s["drop"], ws=self.sel_ws)
+            rows, other = s["y_keep"], s["rows2"]
+            for i in range(c0, min(c0 + chunk, nb)):
+                w, K, V = self.blocks[i]
+                if i == c0:
+                    fv.fvar_block_forward_pruned(self.ctx, w, x, B, M, s["keep"], k, K, V, self.cap,
+                                                 s["Lp"], rows, self.ws)
+                else:
+                    fv.fvar_block_forward_dense(self.ctx, w, rows, B, k, K, V, self.cap, s["Lp"],
+                                                other, self.ws)
+                    rows, other = other, rows
+            fv.fvar_lowrank_fill(self.ctx, rows, s["keep"], s["drop"], B, M, k, r, s["Wc"][c0],
+                                 s["Gc"][c0], y)
+            x = y
+        return x
+
     def factors(self, side):
         """W_c, G_c of the cached counterpart feature of one block at one scale."""
         fv, W, s = self.fv, self.W, self.rp_state(side)
@@ -204,6 +232,15 @@ def variants(chain, W, fv, torch, steps):
             chain.rp_scale(side)
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
+    for side in W.late_scales:
+        chain.chunked_scale(side)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for side in W.late_scales:
+            chain.chunked_scale(side)
+    torch.cuda.synchronize()
+    ms_chunk = (time.perf_counter() - t0) * 1e3 / steps
     fv.fvar_profile_enable(chain.ctx, True)
     rp_k, fac = {}, {}
     for side in W.late_scales:
@@ -242,7 +279,9 @@ def variants(chain, W, fv, torch, steps):
         fv.fvar_profile_enable(chain.ctx, False)
         for k in ("C_all", "W_all", "G_all", "fws_all"):
             chain.scale[side].pop(k)
-    return {"rp_input_path": {"ms_per_step": ms, "tokens_per_s": tokens / (ms * 1e-3), "kernels": rp_k},
+    return {"selection_per_chunk_of_4_blocks": {"ms_per_step": ms_chunk,
+                                                "tokens_per_s": tokens / (ms_chunk * 1e-3)},
+            "rp_input_path": {"ms_per_step": ms, "tokens_per_s": tokens / (ms * 1e-3), "kernels": rp_k},
             "cache_factors": fac}
 
 

@@ -278,3 +278,48 @@ def test_upsampled_thin_factor_feeds_the_fill():
         # statement the bf16 storage of Up(W_c) and of the output both count, hence the wider bound
         full = upsample.upsample_tokens(Wo.astype(np.float64) @ Go.astype(np.float64), hs, hs, hd, hd)
         assert rel_err(to_np(y[b])[drop[b]], full[drop[b]]) <= 2.5 * TOL[dtype]
+
+
+# ----------------------------------------------------------------------------- one selection per chunk
+@pytest.mark.parametrize("dtype,B,M,k,d,H,Lp,r,nblk", [
+    ("bf16", 2, 144, 58, 256, 4, 100, 16, 3),
+    ("f32", 1, 64, 20, 128, 2, 40, 8, 2),
+])
+def test_block_chunk_with_one_selection(dtype, B, M, k, d, H, Lp, r, nblk):
+    """Select once, gather once, run the chunk's blocks on the compact rows, fill once: the
+    existing entry points chained (pruned call for the first block, the dense call on k rows for
+    the others) against the oracle's chunk."""
+    bf = dtype == "bf16"
+    x = wl.activations_lowrank(B, M, d, seed=400, bf16=bf)
+    ws = [wl.block_weights(d, 4 * d, seed=401 + i, bf16=bf, std=0.8 / np.sqrt(d)) for i in range(nblk)]
+    kvs = [wl.kv_prefix(B, Lp, H, d // H, seed=420 + i, bf16=bf) for i in range(nblk)]
+    Cm = wl.cached_feature(B, M, d, r, seed=430, noise=0.05)
+    z = wl.normal_draws(B, M, r, seed=431)
+    Wc = np.empty((B, M, r), np.float32); Gc = np.empty((B, r, d), np.float32)
+    for b in range(B):
+        Wc[b], Gc[b] = factors.cache_factors(Cm[b], z[b])
+    if bf:
+        Wc, Gc = wl.round_to_bf16(Wc), wl.round_to_bf16(Gc)
+    blks = [GpuBlock(d, H, 4 * d, dtype, ws[i], kvs[i][0], kvs[i][1], Lp + k) for i in range(nblk)]
+    xd = to_dev(x, dtype)
+    s, keep, drop = blks[0].score_select(xd, k)
+    rows = blks[0].pruned(xd, keep, k)
+    for blk in blks[1:]:
+        rows = blk.dense(rows)
+    y = blks[0].fill(rows, keep, drop, M, to_dev(Wc, dtype), to_dev(Gc, dtype))
+    torch.cuda.synchronize()
+    for b in range(B):
+        caches = []
+        for i in range(nblk):
+            Kc = np.zeros((Lp + k, H, d // H), np.float32); Vc = np.zeros_like(Kc)
+            Kc[:Lp], Vc[:Lp] = kvs[i][0][b], kvs[i][1][b]
+            caches.append((Kc, Vc))
+        ref = oracle.pruned_chunk(x[b], k, [oracle.BlockWeights(**w) for w in ws], H, caches, Lp,
+                                  Wc[b], Gc[b])
+        assert np.array_equal(keep[b].cpu().numpy(), ref["idx_keep"])
+        assert np.array_equal(drop[b].cpu().numpy(), ref["idx_drop"])
+        assert rel_err(to_np(rows[b]), ref["y_keep"]) <= TOL[dtype], rel_err(to_np(rows[b]), ref["y_keep"])
+        assert rel_err(to_np(y[b]), ref["y"]) <= TOL[dtype]
+        for i in range(nblk):
+            assert rel_err(to_np(blks[i].K[b, Lp:]), caches[i][0][Lp:]) <= TOL[dtype]
+            assert rel_err(to_np(blks[i].V[b, Lp:]), caches[i][1][Lp:]) <= TOL[dtype]
