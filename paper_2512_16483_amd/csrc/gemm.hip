@@ -71,7 +71,7 @@ __device__ __forceinline__ int lds_off(int row, int chunk)      // in bf16 eleme
 // instruction covers whole 128-byte row segments.  The destination row pointers (plain output,
 // or the K / V cache rows of the sample the row belongs to) are computed once per chunk.
 template <int FM, int FN, bool F32_STAGED>
-__device__ __forceinline__ void store_tile_epilogue(floatx16_t (&acc)[FM][FN], const EpiParams &ep,
+__device__ __forceinline__ void store_tile_epilogue(const floatx16_t (*acc)[FN], const EpiParams &ep,
                                                     int rows, int N, int wrow0, int wcol0, int lane,
                                                     uint16_t *wlds)
 {
@@ -208,18 +208,23 @@ __device__ __forceinline__ void dma_b128(const void *base, uint32_t byte_off, ui
                  :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
 }
 
-// LDS needed after the main loop: k-split reduction buffer + one staging tile per wavefront
+// LDS needed after the main loop: k-split reduction buffer + one staging tile per wavefront.
+// A wavefront whose sub-tile is taller than 128 rows sends it through the epilogue in two parts
+// (epi_frags() 32-row fragments at a time), so its staging tile never exceeds 128 rows.
 constexpr size_t kLdsLimit = 160 * 1024;
 constexpr size_t gemm_red_bytes(int BM, int BN, int KS) { return KS > 1 ? (size_t)BM * BN * 4 : 0; }
+constexpr int epi_frags(int FM) { return FM > 4 ? (FM + 1) / 2 : FM; }
+constexpr int epi_rows(int BM, int WM) { return 32 * epi_frags(BM / WM / 32) * WM; }   // all wavefronts
 constexpr bool gemm_f32_staging_fits(int BM, int BN, int WM, int WN, int KS)
 {
-    return gemm_red_bytes(BM, BN, KS) + (size_t)BM * (BN / WN + 4) * WN * 4 <= kLdsLimit;
+    return gemm_red_bytes(BM, BN, KS) + (size_t)epi_rows(BM, WM) * (BN / WN + 4) * WN * 4 <= kLdsLimit;
 }
 constexpr size_t gemm_epi_lds_bytes(int BM, int BN, int WM, int WN, int KS)
 {
     return gemm_red_bytes(BM, BN, KS) +
-           (gemm_f32_staging_fits(BM, BN, WM, WN, KS) ? (size_t)BM * (BN / WN + 4) * WN * 4
-                                                      : (size_t)BM * (BN / WN + 8) * WN * 2);
+           (gemm_f32_staging_fits(BM, BN, WM, WN, KS)
+                ? (size_t)epi_rows(BM, WM) * (BN / WN + 4) * WN * 4
+                : (size_t)epi_rows(BM, WM) * (BN / WN + 8) * WN * 2);
 }
 
 // KS > 1 splits every k-tile between KS groups of WM x WN wavefronts (group ks takes the 16-wide
@@ -371,11 +376,15 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     // per-wavefront staging region behind the reduction buffer: bf16 tile, or fp32 tile when the
     // output is fp32 and it fits (epi_lds_bytes() below is what the launcher allocates)
     constexpr bool F32_STAGED = gemm_f32_staging_fits(BM, BN, WM, WN, KS);
-    constexpr int WREGION = F32_STAGED ? TM * (TN + 4) * 4 : TM * (TN + 8) * 2;    // bytes
+    constexpr int FE = epi_frags(FM);                     // fragments per epilogue pass
+    constexpr int WREGION = F32_STAGED ? FE * 32 * (TN + 4) * 4 : FE * 32 * (TN + 8) * 2;    // bytes
     uint16_t *wlds = reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(lds_raw) + RED_FLOATS * 4 +
                                                   wsub * WREGION);
-    store_tile_epilogue<FM, FN, F32_STAGED>(acc, ep, rows, N, row0 + wm * TM, col0 + wn * TN, lane,
+    store_tile_epilogue<FE, FN, F32_STAGED>(acc, ep, rows, N, row0 + wm * TM, col0 + wn * TN, lane,
                                             wlds);
+    if constexpr (FE < FM)
+        store_tile_epilogue<FM - FE, FN, F32_STAGED>(acc + FE, ep, rows, N, row0 + wm * TM + FE * 32,
+                                                     col0 + wn * TN, lane, wlds);
 }
 
 template <int BM, int BN, int WM, int WN, int STAGES, int KS = 1>
@@ -476,11 +485,11 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
         // cost = rounds of workgroups over the 256 CUs (one workgroup per CU at these LDS sizes)
         // x tile area / sustained rate of the configuration (TFLOP/s measured on large problems)
         struct Cand { int bm, bn; double rate; };
-        const Cand cands[4] = {{256, 256, 1155.0}, {256, 128, 1045.0}, {128, 256, 1041.0},
-                               {128, 128, 1000.0}};
+        const Cand cands[6] = {{256, 256, 1155.0}, {256, 128, 1045.0}, {128, 256, 1041.0},
+                               {128, 128, 1000.0}, {320, 256, 1200.0}, {192, 256, 1100.0}};
         int best = 0;
         double best_cost = 1e300;
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 6; ++i) {
             const long tiles = (long)((rows + cands[i].bm - 1) / cands[i].bm) *
                                ((N + cands[i].bn - 1) / cands[i].bn);
             double rate = cands[i].rate;
@@ -492,6 +501,8 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
         case 0: launch_gemm_bf16_cfg<256, 256, 2, 4, 2>(A, W, rows, N, K, ep, st); break;
         case 1: launch_gemm_bf16_cfg<256, 128, 4, 2, 3>(A, W, rows, N, K, ep, st); break;
         case 2: launch_gemm_bf16_cfg<128, 256, 2, 4, 3>(A, W, rows, N, K, ep, st); break;
+        case 4: launch_gemm_bf16_cfg<320, 256, 2, 4, 2>(A, W, rows, N, K, ep, st); break;
+        case 5: launch_gemm_bf16_cfg<192, 256, 2, 4, 2>(A, W, rows, N, K, ep, st); break;
         default: launch_gemm_bf16_cfg<128, 128, 2, 2, 3, 2>(A, W, rows, N, K, ep, st); break;
         }
     } else {
