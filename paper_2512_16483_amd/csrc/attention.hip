@@ -112,7 +112,28 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
     // explicit vmcnt wait further down the same straight-line block.
     intx4_t kreg[LK];
     intx4_t vreg[LV][4];
+    // byte offsets of this thread's chunks inside a tile that lies wholly inside the cache: such a
+    // tile is fetched as (uniform tile base) + (these constants); only a tile that reaches past
+    // row L-1 pays for the per-row clamp
+    uint32_t k_off[LK], v_off[LV][4];
+#pragma unroll
+    for (int i = 0; i < LK; ++i) k_off[i] = (uint32_t)(((size_t)k_row[i] * rowpitch + k_chk[i] * 8) * 2);
+#pragma unroll
+    for (int i = 0; i < LV; ++i)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+            v_off[i][jj] = (uint32_t)(((size_t)(v_t0[i] + jj) * rowpitch + v_col[i]) * 2);
     auto load_tile = [&](int t0) {
+        if (t0 + BT <= L) {                                  // uniform
+            const uint16_t *kt = Kb + (size_t)t0 * rowpitch, *vtile = Vb + (size_t)t0 * rowpitch;
+#pragma unroll
+            for (int i = 0; i < LK; ++i) kreg[i] = global_load_b128(kt, k_off[i]);
+#pragma unroll
+            for (int i = 0; i < LV; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) vreg[i][jj] = global_load_b128(vtile, v_off[i][jj]);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < LK; ++i) {
             const int t = min(t0 + k_row[i], L - 1);
@@ -139,6 +160,16 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) asm volatile("" : "+v"(vreg[i][jj]));
     };
+    // Lanes of odd column blocks store the odd row of each row pair first, so that one store
+    // instruction touches rows of both parities (both halves of the 64 banks); which half of the
+    // byte permute goes first is folded into per-thread selector constants.
+    uint32_t v_sel[LV][2];
+#pragma unroll
+    for (int i = 0; i < LV; ++i) {
+        const bool flip = (v_col[i] >> 3) & 1;
+        v_sel[i][0] = flip ? 0x07060302u : 0x05040100u;
+        v_sel[i][1] = flip ? 0x05040100u : 0x07060302u;
+    }
     auto store_tile = [&](uint16_t *st) {
 #pragma unroll
         for (int i = 0; i < LK; ++i)
@@ -148,20 +179,17 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
 #pragma unroll
         for (int i = 0; i < LV; ++i) {
             const int chunk = v_dst[i] >> 3, sub = v_dst[i] & 7;
+            const int par = (v_col[i] >> 3) & 1;
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                uint2 lo, hi;
-                lo.x = __builtin_amdgcn_perm(vreg[i][1][m], vreg[i][0][m], 0x05040100u);
-                lo.y = __builtin_amdgcn_perm(vreg[i][3][m], vreg[i][2][m], 0x05040100u);
-                hi.x = __builtin_amdgcn_perm(vreg[i][1][m], vreg[i][0][m], 0x07060302u);
-                hi.y = __builtin_amdgcn_perm(vreg[i][3][m], vreg[i][2][m], 0x07060302u);
-                // lanes of odd column blocks store the odd row first: every store instruction then
-                // touches rows of both parities, i.e. both halves of the 64 banks
-                const bool flip = (v_col[i] >> 3) & 1;
-                const int d0 = v_col[i] + 2 * m, d1 = d0 + 1;
-                const int ra = flip ? d1 : d0, rb = flip ? d0 : d1;
-                *reinterpret_cast<uint2 *>(vt + ra * BT + ((chunk ^ vt_swz(ra)) << 3) + sub) = flip ? hi : lo;
-                *reinterpret_cast<uint2 *>(vt + rb * BT + ((chunk ^ vt_swz(rb)) << 3) + sub) = flip ? lo : hi;
+                uint2 first, second;
+                first.x = __builtin_amdgcn_perm(vreg[i][1][m], vreg[i][0][m], v_sel[i][0]);
+                first.y = __builtin_amdgcn_perm(vreg[i][3][m], vreg[i][2][m], v_sel[i][0]);
+                second.x = __builtin_amdgcn_perm(vreg[i][1][m], vreg[i][0][m], v_sel[i][1]);
+                second.y = __builtin_amdgcn_perm(vreg[i][3][m], vreg[i][2][m], v_sel[i][1]);
+                const int ra = v_col[i] + 2 * m + par, rb = v_col[i] + 2 * m + (par ^ 1);
+                *reinterpret_cast<uint2 *>(vt + ra * BT + ((chunk ^ vt_swz(ra)) << 3) + sub) = first;
+                *reinterpret_cast<uint2 *>(vt + rb * BT + ((chunk ^ vt_swz(rb)) << 3) + sub) = second;
             }
         }
     };
