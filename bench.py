@@ -24,7 +24,7 @@ WORKLOAD = "var_d30_512_bf16"
 # HBM-side bytes per GEMM launch (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size;
 # profiles/pruned_chain_var_d30_512_hbm_counters.txt).  Set to None whenever gemm.hip changes
 # until the counters are taken again.
-GEMM_TRAFFIC_BYTES = 172.4e6
+GEMM_TRAFFIC_BYTES = 166.9e6
 
 
 class Chain:
