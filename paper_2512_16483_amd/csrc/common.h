@@ -77,7 +77,7 @@ __device__ __forceinline__ double wave_sum(double v)
 }
 
 // ---------------------------------------------------------------- launcher interface
-// Every launcher only enqueues kernels on `st`; shapes are validated by the callers in api.cpp.
+// Every launcher only enqueues kernels on `st`; shapes are validated by the callers in api.hip.
 namespace fvar {
 
 enum class DType : int { F32 = 0, BF16 = 1 };
