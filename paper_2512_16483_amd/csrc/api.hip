@@ -55,14 +55,15 @@ hipEvent_t get_event(fvar_ctx *c)
     return e;
 }
 
-// Runs `launch` (one kernel) with its start/stop recorded in an event pair when profiling is on.
+// Runs `launch` (the kernels of one step) with their start/stop recorded in an event pair when
+// profiling is on.
 template <typename F>
 void timed(fvar_ctx *c, hipStream_t st, const char *label, F &&launch)
 {
     if (!c->profiling) { launch(); return; }
     fvar_ctx::Rec r{label, get_event(c), get_event(c)};
-    fvar::LaunchProbe probe{r.a, r.b};
-    fvar::g_probe = &probe;                   // the (single) kernel launch inside records into it
+    fvar::LaunchProbe probe{r.a, r.b, false};
+    fvar::g_probe = &probe;                   // the kernel launches inside record into it
     launch();
     fvar::g_probe = nullptr;
     (void)st;
@@ -78,7 +79,7 @@ fvar_status launch_status(fvar_ctx *c, const char *what)
 }
 
 struct BlockWs {
-    char *x_keep, *u, *q, *att, *h1, *hid;
+    char *x_keep, *u, *q, *att, *h1, *hid, *att_part;
     size_t total;
 };
 
@@ -95,6 +96,9 @@ BlockWs carve(const fvar_ctx *c, void *ws, int B, int rows)
     w.att = take(R * d * es);
     w.h1 = take(R * d * sizeof(float));       // intermediate residual stream, always fp32
     w.hid = take(R * F * es);
+    // partial attention results when the key axis is split between workgroups (small batches)
+    const int splits = fvar::attention_max_splits(dtype(c), B, rows, c->cfg.heads, c->cfg.head_dim);
+    w.att_part = splits > 1 ? take((size_t)splits * R * (d + 2 * c->cfg.heads) * sizeof(float)) : nullptr;
     w.total = off;
     return w;
 }
@@ -147,7 +151,7 @@ fvar_status block_forward(fvar_ctx *c, hipStream_t st, const fvar_block_weights 
     });
     timed(c, st, "attention", [&] {
         fvar::launch_attention(dt, s.q, kv->k, kv->v, B, rows, L, kv->capacity, H, Dh, c->scale, s.att,
-                               st);
+                               reinterpret_cast<float *>(s.att_part), st);
     });
     timed(c, st, "gemm_o", [&] {
         fvar::GemmEpilogue e;

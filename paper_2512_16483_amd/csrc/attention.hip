@@ -50,7 +50,10 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
                                                         const uint16_t *__restrict__ Kc,
                                                         const uint16_t *__restrict__ Vc, int n, int L,
                                                         int cap, int H, float c_log2,
-                                                        uint16_t *__restrict__ o)
+                                                        uint16_t *__restrict__ o, int nsplit,
+                                                        int tiles_per_split,
+                                                        float *__restrict__ part_o,
+                                                        float *__restrict__ part_ml)
 {
     constexpr int KS = DH / 16;              // k16 steps of the QK product
     constexpr int DB = DH / 32;              // 32-row blocks of O^T
@@ -65,7 +68,9 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int rl = lane & 31, g = lane >> 5;
-    const int h = blockIdx.y, b = blockIdx.z;
+    // blockIdx.z = sample * nsplit + split: with nsplit > 1 this workgroup sees only the key tiles
+    // [tile0, tile1) and leaves an unnormalised partial result for the merge kernel
+    const int h = blockIdx.y, b = blockIdx.z / nsplit, split = blockIdx.z % nsplit;
     const int q0 = blockIdx.x * (128 * NQ) + wave * (32 * NQ);
     const bool wave_active = __builtin_amdgcn_readfirstlane(q0 < n ? 1 : 0) != 0;
     const size_t rowpitch = (size_t)H * DH;
@@ -203,7 +208,9 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
 #pragma unroll
     for (int j = 0; j < NQ; ++j) { m_run[j] = -INFINITY; l_run[j] = 0.f; }
 
-    load_tile(0);
+    const int tile0 = split * tiles_per_split;
+    const int tile1 = min((L + BT - 1) / BT, tile0 + tiles_per_split);
+    load_tile(tile0 * BT);
     wait_tile();
     store_tile(lds);
     // the Q fragments are consumed here once so that the compiler's own wait for their loads
@@ -214,11 +221,12 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
         for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(qf[j][s]));
     __syncthreads();
 
-    const int ntiles = (L + BT - 1) / BT;
-    // one key tile; MASKED is set only for the last tile, whose ragged tail must not contribute
-    auto tile = [&](int it, auto masked) {
+    // one key tile (`it` counts from this workgroup's first tile); MASKED is set only for the
+    // last tile, whose ragged tail must not contribute
+    auto tile = [&](int lt, auto masked) {
         constexpr bool MASKED = decltype(masked)::value;
-        const uint16_t *ks = lds + (it & 1) * STAGE;
+        const int it = tile0 + lt;
+        const uint16_t *ks = lds + (lt & 1) * STAGE;
         const uint16_t *vt = ks + KTILE;
         // next tile (row indices are clamped, so the request past the end is harmless)
         load_tile((it + 1) * BT);
@@ -316,11 +324,34 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
         }
         }
         wait_tile();
-        store_tile(lds + ((it + 1) & 1) * STAGE);
+        store_tile(lds + ((lt + 1) & 1) * STAGE);
         __syncthreads();
     };
-    for (int it = 0; it + 1 < ntiles; ++it) tile(it, std::false_type{});
-    tile(ntiles - 1, std::true_type{});
+    const int nloc = tile1 - tile0;
+    for (int lt = 0; lt + 1 < nloc; ++lt) tile(lt, std::false_type{});
+    tile(nloc - 1, std::true_type{});
+
+    if (nsplit > 1) {
+        // partial result of this key range: unnormalised O (fp32), running max and sum
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+            const int row = q0 + j * 32 + rl;
+            const float l = l_run[j] + __shfl_xor(l_run[j], 32);
+            if (row >= n) continue;
+            const size_t prow = ((size_t)(b * nsplit + split) * n + row) * H + h;
+            float *dst = part_o + prow * DH;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; e += 4) {
+                    const int dh = db * 32 + 8 * (e >> 2) + 4 * g;
+                    *reinterpret_cast<float4 *>(dst + dh) = make_float4(
+                        oacc[db][j][e], oacc[db][j][e + 1], oacc[db][j][e + 2], oacc[db][j][e + 3]);
+                }
+            if (g == 0) *reinterpret_cast<float2 *>(part_ml + prow * 2) = make_float2(m_run[j], l);
+        }
+        return;
+    }
 
     // ---- normalise and store: lane = query, 4 consecutive head-dim values per accumulator group
 #pragma unroll
@@ -343,9 +374,66 @@ __global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(cons
     }
 }
 
+// Merge of the key-range partials: o = sum_s O_s w_s / sum_s l_s w_s with w_s = 2^((m_s - max m) c).
+// One thread per 4 consecutive head-dim values of one (sample, query row, head).
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part_o,
+                                                         const float *__restrict__ part_ml, int n,
+                                                         int H, int DH, int nsplit, float c_log2,
+                                                         long total, uint16_t *__restrict__ o)
+{
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;       // over B * n * H * DH/4
+    if (idx >= total) return;
+    const int per_row = H * (DH / 4);
+    const long brow = idx / per_row;                             // b * n + row
+    const int rem = (int)(idx % per_row), h = rem / (DH / 4), c4 = rem % (DH / 4);
+    const long b = brow / n, row = brow % n;
+    float m = -INFINITY;
+    for (int s = 0; s < nsplit; ++s)
+        m = fmaxf(m, part_ml[((((size_t)b * nsplit + s) * n + row) * H + h) * 2]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float den = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        const size_t prow = (((size_t)b * nsplit + s) * n + row) * H + h;
+        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + prow * 2);
+        const float w = __builtin_amdgcn_exp2f((ml.x - m) * c_log2);
+        const float4 v = *reinterpret_cast<const float4 *>(part_o + prow * DH + c4 * 4);
+        acc.x = fmaf(v.x, w, acc.x); acc.y = fmaf(v.y, w, acc.y);
+        acc.z = fmaf(v.z, w, acc.z); acc.w = fmaf(v.w, w, acc.w);
+        den = fmaf(ml.y, w, den);
+    }
+    const float inv = 1.0f / den;
+    uint2 pk;
+    pk.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+    pk.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+    *reinterpret_cast<uint2 *>(o + ((size_t)brow * H + h) * DH + c4 * 4) = pk;
+}
+
+// Number of key ranges for a problem, from the launch geometry alone (not the cache length, so
+// that the workspace can be sized from it; the launcher lowers it when the cache is short).
+// The kernel is throughput-bound per CU, so what counts is rounds of workgroups over the 256 CUs:
+// s ranges cost ceil(wgs*s/256)/s rounds of full-length work, plus about 8 % per extra range for
+// the partial results and their merge (fitted to the head_dim-128 shapes with 64..640 workgroups).
+int attention_max_splits(DType dt, int B, int n, int H, int Dh)
+{
+    if (dt != DType::BF16) return 1;
+    const bool wide = Dh == 64 && ((n % 256 == 0) || (n % 256 > 128));
+    const long wgs = (long)((n + (wide ? 255 : 127)) / (wide ? 256 : 128)) * H * B;
+#ifdef FVAR_ATTN_SPLIT_OVERRIDE
+    if (FVAR_ATTN_SPLIT_OVERRIDE > 0) return FVAR_ATTN_SPLIT_OVERRIDE;      // tuning harness only
+#endif
+    int best = 1;
+    double best_cost = 1e300;
+    for (int s = 1; s <= 8; ++s) {
+        const double rounds = (double)((wgs * s + 255) / 256);
+        const double cost = rounds / s * (1.0 + 0.08 * (s - 1));
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
+    }
+    return best;
+}
+
 template <int DH, int NQ>
 static void launch_attn_bf16(const void *q, const void *K, const void *V, int B, int n, int L,
-                             int cap, int H, float scale, void *o, hipStream_t st)
+                             int cap, int H, float scale, void *o, float *part, hipStream_t st)
 {
     constexpr int BQ = 128 * NQ;
     const size_t lds = (size_t)2 * 2 * BT * DH * sizeof(uint16_t);
@@ -356,10 +444,25 @@ static void launch_attn_bf16(const void *q, const void *K, const void *V, int B,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
-    dim3 grid((n + BQ - 1) / BQ, H, B), block(256);
+    // key ranges: every range at least 4 tiles long, none empty
+    const int ntiles = (L + BT - 1) / BT;
+    int nsplit = part ? attention_max_splits(DType::BF16, B, n, H, DH) : 1;
+    if (nsplit > ntiles / 4) nsplit = ntiles / 4 > 0 ? ntiles / 4 : 1;
+    int tps = (ntiles + nsplit - 1) / nsplit;
+    nsplit = (ntiles + tps - 1) / tps;
+    const float c_log2 = scale * 1.4426950408889634f;
+    float *part_o = part;
+    float *part_ml = part ? part + (size_t)nsplit * B * n * H * DH : nullptr;
+    dim3 grid((n + BQ - 1) / BQ, H, B * nsplit), block(256);
     launch(kern, grid, block, lds, st, (const uint16_t *)q, (const uint16_t *)K,
-                       (const uint16_t *)V, n, L, cap, H, scale * 1.4426950408889634f,
-                       (uint16_t *)o);
+                       (const uint16_t *)V, n, L, cap, H, c_log2, (uint16_t *)o, nsplit, tps, part_o,
+                       part_ml);
+    if (nsplit > 1) {
+        const long total = (long)B * n * H * (DH / 4);
+        launch(attn_merge_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+               (const float *)part_o, (const float *)part_ml, n, H, DH, nsplit, c_log2, total,
+               (uint16_t *)o);
+    }
 }
 
 // ------------------------------------------------------------------------------ fp32
@@ -439,18 +542,18 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
 }
 
 void launch_attention(DType dt, const void *q, const void *K, const void *V, int B, int n, int L,
-                      int cap, int H, int Dh, float scale, void *o, hipStream_t st)
+                      int cap, int H, int Dh, float scale, void *o, float *part, hipStream_t st)
 {
     if (dt == DType::BF16) {
         // two 32-query blocks per wavefront halve the LDS operand traffic per MFMA; use the
         // single-block variant when that would leave most of a 256-query tile empty
         const bool wide = (n % 256 == 0) || (n % 256 > 128);
         if (Dh == 64) {
-            if (wide) launch_attn_bf16<64, 2>(q, K, V, B, n, L, cap, H, scale, o, st);
-            else launch_attn_bf16<64, 1>(q, K, V, B, n, L, cap, H, scale, o, st);
+            if (wide) launch_attn_bf16<64, 2>(q, K, V, B, n, L, cap, H, scale, o, part, st);
+            else launch_attn_bf16<64, 1>(q, K, V, B, n, L, cap, H, scale, o, part, st);
         } else {
             // head_dim 128 with two query blocks per wavefront does not fit the register file
-            launch_attn_bf16<128, 1>(q, K, V, B, n, L, cap, H, scale, o, st);
+            launch_attn_bf16<128, 1>(q, K, V, B, n, L, cap, H, scale, o, part, st);
         }
     } else {
         dim3 grid((n + 31) / 32, H, B), block(256);

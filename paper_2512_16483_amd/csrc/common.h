@@ -84,17 +84,20 @@ enum class DType : int { F32 = 0, BF16 = 1 };
 
 // Kernel launch used by every launcher.  While per-kernel timing is switched on, the API layer
 // points g_probe at an event pair and the launch records the kernel's own start and stop in it
-// (hipExtLaunchKernel), which excludes the dispatch gap between consecutive kernels.
-struct LaunchProbe { hipEvent_t start, stop; };
+// (hipExtLaunchKernel), which excludes the dispatch gap in front of the step.
+// A step that launches several kernels records the start of its first and the stop of its last.
+struct LaunchProbe { hipEvent_t start, stop; bool started; };
 extern thread_local LaunchProbe *g_probe;
 template <typename F, typename... Args>
 inline void launch(F kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args)
 {
-    if (g_probe)
-        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, g_probe->start, g_probe->stop, 0,
-                              args...);
-    else
+    if (g_probe) {
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st,
+                              g_probe->started ? nullptr : g_probe->start, g_probe->stop, 0, args...);
+        g_probe->started = true;
+    } else {
         hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+    }
 }
 
 // scores[b,i] = fl32(sum_j x[b,i,j]^2), fp64 accumulation
@@ -136,8 +139,13 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
 
 // o[b,i,h,:] = softmax_t(scale * q[b,i,h,:] . K[b,t,h,:]) V[b,t,h,:], t in [0,L)
 //   q,o:[B,n,H,Dh]; K,V:[B,cap,H,Dh]
+// `part`: scratch for splitting the key axis between workgroups when the problem has too few
+// (query block, head, sample) triples to fill the chip, or null (never split):
+// attention_max_splits() * B*n*H*(Dh + 2) floats.  With more than one key range a second kernel
+// merges the partial results.
+int attention_max_splits(DType dt, int B, int n, int H, int Dh);
 void launch_attention(DType dt, const void *q, const void *K, const void *V, int B, int n, int L,
-                      int cap, int H, int Dh, float scale, void *o, hipStream_t st);
+                      int cap, int H, int Dh, float scale, void *o, float *part, hipStream_t st);
 
 // y[b,idx_keep[b,j],:] = y_keep[b,j,:];  y[b,i,:] = w_c[b,i,:] g_c[b] for i in idx_drop[b,:]
 void launch_fill(DType dt, const void *y_keep, const int32_t *idx_keep, const int32_t *idx_drop,

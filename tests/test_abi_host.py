@@ -38,8 +38,13 @@ def test_keep_count_and_schedule_helpers():
     assert fv.fvar_scale_prev_len(c, 10) == 2521 and fv.fvar_scale_tokens(c, 13) == -1
     r = fv.Context(hidden=128, heads=2, head_dim=64, ffn_hidden=256, scales=((3, 5), (4, 7)))
     assert fv.fvar_scale_tokens(r, 1) == 28 and fv.fvar_scale_prev_len(r, 1) == 15
-    # workspace: four [rows,d] buffers, the fp32 residual stream [rows,d] and one [rows,F] buffer
-    assert fv.fvar_block_workspace_bytes(r, 2, 10) == 4 * 5120 + 10240 + 10240
+    # workspace: four [rows,d] buffers, the fp32 residual stream [rows,d], one [rows,F] buffer and,
+    # for a problem this small, 8 key-range partials of the attention ([rows,d] + 2 [rows,H] fp32)
+    assert fv.fvar_block_workspace_bytes(r, 2, 10) == 4 * 5120 + 10240 + 10240 + 8 * 20 * (128 + 4) * 4
+    big = fv.Context(hidden=1920, heads=30, head_dim=64, ffn_hidden=7680)
+    rows = 8 * 410
+    assert fv.fvar_block_workspace_bytes(big, 8, 410) == sum(
+        (n + 255) // 256 * 256 for n in [rows * 1920 * 2] * 4 + [rows * 1920 * 4, rows * 7680 * 2])
     assert fv.fvar_select_workspace_bytes(r, 3, 100) == 1280
 
 

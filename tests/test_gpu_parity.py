@@ -128,6 +128,8 @@ SMALL = [  # dtype, B, M, d, H, F, Lp, k, r
     ("bf16", 2, 130, 192, 3, 448, 0, 67, 16),        # empty cache prefix: only the new rows are keys
     ("bf16", 3, 520, 256, 2, 1024, 300, 257, 64),    # head_dim 128, several samples, k just over a tile
     ("f32", 1, 64, 64, 1, 64, 0, 64, 4),             # smallest geometry, nothing cached, keep all
+    ("bf16", 1, 160, 256, 2, 512, 1500, 64, 16),     # batch 1, long cache: key axis split 5 ways (head_dim 128)
+    ("bf16", 1, 300, 128, 2, 256, 1000, 150, 16),    # the same with head_dim 64 and two query blocks per wavefront
 ]
 
 
@@ -273,4 +275,11 @@ def test_head_dim_128_workloads_real_shape(name, side, B):
     assert rel_err(to_np(blk.K[:, Lp:Lp + k]), ref["K_new"]) <= 2e-2
     assert rel_err(to_np(blk.V[:, Lp:Lp + k]), ref["V_new"]) <= 2e-2
     assert rel_err(to_np(y_keep), ref["y_keep"]) <= 2e-2
-    assert rel_err(to_np(y), ref["y"]) <= 2e-2
+    # The scattered map, part by part: kept rows are the rows of y_keep bit for bit, restored rows
+    # meet the bar against the oracle's restored rows.  (Kept rows are the high-energy rows and the
+    # restored rows of this workload are unit-variance, so one rms floor over the mixed tensor
+    # would judge the kept rows' small elements against the wrong magnitude.)
+    yg, kk, dd = to_np(y), ref["idx_keep"], ref["idx_drop"]
+    for b in range(B):
+        assert np.array_equal(yg[b][kk[b]], to_np(y_keep[b]))
+        assert rel_err(yg[b][dd[b]], ref["y"][b][dd[b]]) <= 2e-2
