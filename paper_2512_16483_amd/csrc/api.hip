@@ -79,7 +79,7 @@ fvar_status launch_status(fvar_ctx *c, const char *what)
 }
 
 struct BlockWs {
-    char *x_keep, *u, *q, *att, *h1, *hid, *att_part;
+    char *x_keep, *u, *q, *att, *h1, *hid, *att_part, *gemm_part;
     size_t total;
 };
 
@@ -99,6 +99,15 @@ BlockWs carve(const fvar_ctx *c, void *ws, int B, int rows)
     // partial attention results when the key axis is split between workgroups (small batches)
     const int splits = fvar::attention_max_splits(dtype(c), B, rows, c->cfg.heads, c->cfg.head_dim);
     w.att_part = splits > 1 ? take((size_t)splits * R * (d + 2 * c->cfg.heads) * sizeof(float)) : nullptr;
+    // partial tiles of the linear layers whose contraction axis is divided between workgroups
+    const DType dt = dtype(c);
+    size_t gp = 0;
+    const size_t shapes[3][2] = {{d, d}, {F, d}, {d, F}};            // (N, K) of O, FC1, FC2
+    for (auto &sh : shapes) {
+        const int ns = fvar::gemm_splits(dt, (int)R, (int)sh[0], (int)sh[1]);
+        if (ns > 1 && ns * R * sh[0] * sizeof(float) > gp) gp = ns * R * sh[0] * sizeof(float);
+    }
+    w.gemm_part = gp ? take(gp) : nullptr;
     w.total = off;
     return w;
 }
@@ -157,6 +166,7 @@ fvar_status block_forward(fvar_ctx *c, hipStream_t st, const fvar_block_weights 
         fvar::GemmEpilogue e;
         e.bias = w->b_o; e.residual = resid; e.out0 = s.h1; e.ld0 = d; e.split = d;
         e.out_f32 = 1;
+        e.splitk_scratch = reinterpret_cast<float *>(s.gemm_part);
         fvar::launch_gemm(dt, s.att, w->w_o, R, d, d, e, st);
     });
     timed(c, st, "ln2", [&] {
@@ -169,11 +179,13 @@ fvar_status block_forward(fvar_ctx *c, hipStream_t st, const fvar_block_weights 
     timed(c, st, "gemm_fc1", [&] {
         fvar::GemmEpilogue e;
         e.bias = w->b_fc1; e.gelu = 1; e.out0 = s.hid; e.ld0 = F; e.split = F;
+        e.splitk_scratch = reinterpret_cast<float *>(s.gemm_part);
         fvar::launch_gemm(dt, s.u, w->w_fc1, R, F, d, e, st);
     });
     timed(c, st, "gemm_fc2", [&] {
         fvar::GemmEpilogue e;
         e.bias = w->b_fc2; e.residual = s.h1; e.res_f32 = 1; e.out0 = y; e.ld0 = d; e.split = d;
+        e.splitk_scratch = reinterpret_cast<float *>(s.gemm_part);
         fvar::launch_gemm(dt, s.hid, w->w_fc2, R, d, F, e, st);
     });
     return launch_status(c, who);

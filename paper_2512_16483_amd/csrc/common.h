@@ -133,7 +133,11 @@ struct GemmEpilogue {
     // Used for the intermediate residual stream h = x + attention projection, which stays in
     // fp32 between the two halves of the block so that it is not rounded twice.
     int out_f32 = 0, res_f32 = 0;
+    // bf16 path: scratch for dividing the contraction axis between workgroups when the problem
+    // has too few tiles to fill the chip, gemm_splits() * rows * N floats, or null (never divide).
+    float *splitk_scratch = nullptr;
 };
+int gemm_splits(DType dt, int rows, int N, int K);
 void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
                  const GemmEpilogue &ep, hipStream_t st);
 

@@ -233,7 +233,7 @@ constexpr size_t gemm_epi_lds_bytes(int BM, int BN, int WM, int WN, int KS)
 template <int BM, int BN, int WM, int WN, int STAGES, int KS>
 __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, int rows, int N, int K,
-    int tiles_m, int tiles_n, int group_m, EpiParams ep)
+    int tiles_m, int tiles_n, int group_m, EpiParams ep, int nsplit, float *__restrict__ part)
 {
     constexpr int NW = WM * WN * KS;                   // wavefronts per workgroup
     constexpr int TM = BM / WM, TN = BN / WN;
@@ -244,10 +244,15 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     extern __shared__ uint4 lds_raw[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds_raw;
 
+    // nsplit > 1: the contraction axis is divided between nsplit workgroups per tile (for problems
+    // with too few tiles to fill the chip); each leaves an fp32 partial tile in `part` and a
+    // second kernel adds them up and applies the epilogue
     const int ntiles = tiles_m * tiles_n;
     const int per_xcd = (gridDim.x + 7) / 8;
     int pid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (pid >= ntiles) return;
+    if (pid >= ntiles * nsplit) return;
+    const int split = pid % nsplit;
+    pid /= nsplit;
     // consecutive tile ids run down group_m row tiles, then across the columns: the contiguous
     // id range of one XCD is a patch of about group_m x (tiles/8/group_m) tiles
     const int group = pid / (group_m * tiles_n);
@@ -279,9 +284,11 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
         const int c = (lane & 7) ^ ((r >> 1) & 7);
         b_off[i] = (uint32_t)(((size_t)min(col0 + r, N - 1) * K + c * 8) * sizeof(uint16_t));
     }
-    const int ktiles = K / BK;
-    auto issue = [&](int kt, int stage) {               // DMA of k-tile kt into `stage`
-        const int koff = kt * BK;
+    const int ktiles_all = K / BK, kper = (ktiles_all + nsplit - 1) / nsplit;
+    const int kt0 = split * kper;
+    const int ktiles = min(ktiles_all, kt0 + kper) - kt0;   // k-tiles of this workgroup (>= 1)
+    auto issue = [&](int kt, int stage) {               // DMA of this workgroup's k-tile kt into `stage`
+        const int koff = (kt0 + kt) * BK;
         const uint32_t sbase = lds_base + stage * STAGE_BYTES + wave * 1024;
 #pragma unroll
         for (int i = 0; i < NGA; ++i) dma_b128(A + koff, a_off[i], sbase + i * (NW * 1024));
@@ -373,6 +380,24 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] += red[((i * FN + j) * 16 + e) * 64];
     }
+    if (nsplit > 1) {
+        // partial tile, fp32, row-major [rows][N]: the 32 lanes of a half-wavefront cover 128
+        // contiguous bytes of a row
+        float *dst = part + (size_t)split * rows * N;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int col = col0 + wn * TN + j * 32 + rl;
+            if (col >= N) continue;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = row0 + wm * TM + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+                    if (row < rows) dst[(size_t)row * N + col] = acc[i][j][e];
+                }
+        }
+        return;
+    }
     // per-wavefront staging region behind the reduction buffer: bf16 tile, or fp32 tile when the
     // output is fp32 and it fits (epi_lds_bytes() below is what the launcher allocates)
     constexpr bool F32_STAGED = gemm_f32_staging_fits(BM, BN, WM, WN, KS);
@@ -389,11 +414,12 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
 
 template <int BM, int BN, int WM, int WN, int STAGES, int KS = 1>
 static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, int K,
-                                 const EpiParams &ep, hipStream_t st)
+                                 const EpiParams &ep, hipStream_t st, int nsplit = 1,
+                                 float *part = nullptr)
 {
     const int tiles_m = (rows + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int ntiles = tiles_m * tiles_n;
-    const int grid = (ntiles + 7) / 8 * 8;
+    const int grid = (ntiles * nsplit + 7) / 8 * 8;
     const size_t lds_stages = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
     const size_t lds_epi = gemm_epi_lds_bytes(BM, BN, WM, WN, KS);
     const size_t lds = lds_stages > lds_epi ? lds_stages : lds_epi;
@@ -412,7 +438,45 @@ static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, 
 #endif
     group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
     launch(kern, dim3(grid), dim3(64 * WM * WN * KS), lds, st, (const uint16_t *)A,
-                       (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, group_m, ep);
+                       (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, group_m, ep, nsplit, part);
+}
+
+// Sum of the partial tiles of a split contraction + the epilogue (bias, GELU, residual, bf16 or
+// fp32 output; never the K/V routing).  One thread per 4 consecutive columns.
+__global__ __launch_bounds__(256) void gemm_splitk_epilogue_kernel(const float *__restrict__ part,
+                                                                   int nsplit, int rows, int N,
+                                                                   EpiParams ep)
+{
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    const int cpr = N / 4;
+    if (idx >= (long)rows * cpr) return;
+    const int row = (int)(idx / cpr), col = (int)(idx % cpr) * 4;
+    const size_t off = (size_t)row * N + col;
+    float4 v = *reinterpret_cast<const float4 *>(part + off);
+    for (int s = 1; s < nsplit; ++s) {
+        const float4 p = *reinterpret_cast<const float4 *>(part + (size_t)s * rows * N + off);
+        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    if (ep.bias) {
+        const uint2 b = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(ep.bias) + col);
+        v.x += bf16_lo(b.x); v.y += bf16_hi(b.x); v.z += bf16_lo(b.y); v.w += bf16_hi(b.y);
+    }
+    if (ep.gelu) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
+    if (ep.residual) {
+        if (ep.res_f32) {
+            const float4 r = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(ep.residual) + off);
+            v.x += r.x; v.y += r.y; v.z += r.z; v.w += r.w;
+        } else {
+            const uint2 r = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(ep.residual) + off);
+            v.x += bf16_lo(r.x); v.y += bf16_hi(r.x); v.z += bf16_lo(r.y); v.w += bf16_hi(r.y);
+        }
+    }
+    const size_t ooff = (size_t)row * ep.ld0 + col;
+    if (ep.out_f32)
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(ep.out0) + ooff) = v;
+    else
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(ep.out0) + ooff) =
+            make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
 }
 
 // ------------------------------------------------------------------------------ fp32 FMA
@@ -469,6 +533,45 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
     }
 }
 
+// Tile configuration for a problem: rounds of workgroups over the 256 CUs (one workgroup per CU
+// at these LDS sizes) x tile area / sustained rate of the configuration (TFLOP/s measured on large
+// problems).  Returns the index into the table and the number of tiles.
+static int pick_bf16_config(int rows, int N, long *tiles_out)
+{
+    struct Cand { int bm, bn; double rate; };
+    const Cand cands[6] = {{256, 256, 1155.0}, {256, 128, 1045.0}, {128, 256, 1041.0},
+                           {128, 128, 1000.0}, {320, 256, 1200.0}, {192, 256, 1100.0}};
+    int best = 0;
+    double best_cost = 1e300;
+    long best_tiles = 0;
+    for (int i = 0; i < 6; ++i) {
+        const long tiles = (long)((rows + cands[i].bm - 1) / cands[i].bm) *
+                           ((N + cands[i].bn - 1) / cands[i].bn);
+        double rate = cands[i].rate;
+        if (i == 3 && tiles > 256) rate = 650.0;       // small tiles pay per round
+        const double cost = (double)((tiles + 255) / 256) * cands[i].bm * cands[i].bn / rate;
+        if (cost < best_cost) { best_cost = cost; best = i; best_tiles = tiles; }
+    }
+    *tiles_out = best_tiles;
+    return best;
+}
+
+// Workgroups per tile along the contraction axis: only when the tiles cover at most half of the
+// CUs, every part at least 4 k-tiles long, at most 8 parts.
+int gemm_splits(DType dt, int rows, int N, int K)
+{
+    if (dt != DType::BF16) return 1;
+    long tiles;
+    (void)pick_bf16_config(rows, N, &tiles);
+    long s = 256 / tiles;
+    const long kmax = K / BK / 4;
+    if (s > kmax) s = kmax;
+    if (s > 8) s = 8;
+    if (s < 2) return 1;
+    const long kt = K / BK, per = (kt + s - 1) / s;
+    return (int)((kt + per - 1) / per);                  // no empty part
+}
+
 void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
                  const GemmEpilogue &e, hipStream_t st)
 {
@@ -482,28 +585,23 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
     ep.out_f32 = e.out_f32;
     ep.res_f32 = e.res_f32;
     if (dt == DType::BF16) {
-        // cost = rounds of workgroups over the 256 CUs (one workgroup per CU at these LDS sizes)
-        // x tile area / sustained rate of the configuration (TFLOP/s measured on large problems)
-        struct Cand { int bm, bn; double rate; };
-        const Cand cands[6] = {{256, 256, 1155.0}, {256, 128, 1045.0}, {128, 256, 1041.0},
-                               {128, 128, 1000.0}, {320, 256, 1200.0}, {192, 256, 1100.0}};
-        int best = 0;
-        double best_cost = 1e300;
-        for (int i = 0; i < 6; ++i) {
-            const long tiles = (long)((rows + cands[i].bm - 1) / cands[i].bm) *
-                               ((N + cands[i].bn - 1) / cands[i].bn);
-            double rate = cands[i].rate;
-            if (i == 3 && tiles > 256) rate = 650.0;       // small tiles pay per round
-            const double cost = (double)((tiles + 255) / 256) * cands[i].bm * cands[i].bn / rate;
-            if (cost < best_cost) { best_cost = cost; best = i; }
-        }
+        long tiles;
+        const int best = pick_bf16_config(rows, N, &tiles);
+        // the K/V routing lives in the in-kernel epilogue only, so the routed launch is never split
+        const int ns = (e.splitk_scratch && e.split == N) ? gemm_splits(dt, rows, N, K) : 1;
+        float *part = ns > 1 ? e.splitk_scratch : nullptr;
         switch (best) {
-        case 0: launch_gemm_bf16_cfg<256, 256, 2, 4, 2>(A, W, rows, N, K, ep, st); break;
-        case 1: launch_gemm_bf16_cfg<256, 128, 4, 2, 3>(A, W, rows, N, K, ep, st); break;
-        case 2: launch_gemm_bf16_cfg<128, 256, 2, 4, 3>(A, W, rows, N, K, ep, st); break;
-        case 4: launch_gemm_bf16_cfg<320, 256, 2, 4, 2>(A, W, rows, N, K, ep, st); break;
-        case 5: launch_gemm_bf16_cfg<192, 256, 2, 4, 2>(A, W, rows, N, K, ep, st); break;
-        default: launch_gemm_bf16_cfg<128, 128, 2, 2, 3, 2>(A, W, rows, N, K, ep, st); break;
+        case 0: launch_gemm_bf16_cfg<256, 256, 2, 4, 2>(A, W, rows, N, K, ep, st, ns, part); break;
+        case 1: launch_gemm_bf16_cfg<256, 128, 4, 2, 3>(A, W, rows, N, K, ep, st, ns, part); break;
+        case 2: launch_gemm_bf16_cfg<128, 256, 2, 4, 3>(A, W, rows, N, K, ep, st, ns, part); break;
+        case 4: launch_gemm_bf16_cfg<320, 256, 2, 4, 2>(A, W, rows, N, K, ep, st, ns, part); break;
+        case 5: launch_gemm_bf16_cfg<192, 256, 2, 4, 2>(A, W, rows, N, K, ep, st, ns, part); break;
+        default: launch_gemm_bf16_cfg<128, 128, 2, 2, 3, 2>(A, W, rows, N, K, ep, st, ns, part); break;
+        }
+        if (ns > 1) {
+            const long total = (long)rows * (N / 4);
+            launch(gemm_splitk_epilogue_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                   (const float *)part, ns, rows, N, ep);
         }
     } else {
         dim3 grid((N + 63) / 64, (rows + 63) / 64), block(256);

@@ -130,6 +130,7 @@ SMALL = [  # dtype, B, M, d, H, F, Lp, k, r
     ("f32", 1, 64, 64, 1, 64, 0, 64, 4),             # smallest geometry, nothing cached, keep all
     ("bf16", 1, 160, 256, 2, 512, 1500, 64, 16),     # batch 1, long cache: key axis split 5 ways (head_dim 128)
     ("bf16", 1, 300, 128, 2, 256, 1000, 150, 16),    # the same with head_dim 64 and two query blocks per wavefront
+    ("bf16", 1, 256, 1024, 16, 4096, 424, 128, 32),  # few tiles, long contraction: linear layers split along k
 ]
 
 
