@@ -46,7 +46,7 @@ __device__ __forceinline__ int vt_swz(int row)
 }
 
 template <int DH, int NQ>
-__global__ __launch_bounds__(256, (DH == 64 ? 2 : 1)) void attn_bf16_kernel(const uint16_t *__restrict__ q,
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__restrict__ q,
                                                         const uint16_t *__restrict__ Kc,
                                                         const uint16_t *__restrict__ Vc, int n, int L,
                                                         int cap, int H, float c_log2,
@@ -412,7 +412,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
 // that the workspace can be sized from it; the launcher lowers it when the cache is short).
 // The kernel is throughput-bound per CU, so what counts is rounds of workgroups over the 256 CUs:
 // s ranges cost ceil(wgs*s/256)/s rounds of full-length work, plus about 8 % per extra range for
-// the partial results and their merge (fitted to the head_dim-128 shapes with 64..640 workgroups).
+// the partial results and their merge (12 % when the problem already fills the chip once: its
+// partials are larger); fitted to sweeps of the head_dim-128 shapes with 64..640 workgroups.
 int attention_max_splits(DType dt, int B, int n, int H, int Dh)
 {
     if (dt != DType::BF16) return 1;
@@ -423,9 +424,10 @@ int attention_max_splits(DType dt, int B, int n, int H, int Dh)
 #endif
     int best = 1;
     double best_cost = 1e300;
+    const double per_split = wgs >= 256 ? 0.12 : 0.08;
     for (int s = 1; s <= 8; ++s) {
         const double rounds = (double)((wgs * s + 255) / 256);
-        const double cost = rounds / s * (1.0 + 0.08 * (s - 1));
+        const double cost = rounds / s * (1.0 + per_split * (s - 1));
         if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
     }
     return best;
@@ -552,7 +554,9 @@ void launch_attention(DType dt, const void *q, const void *K, const void *V, int
             if (wide) launch_attn_bf16<64, 2>(q, K, V, B, n, L, cap, H, scale, o, part, st);
             else launch_attn_bf16<64, 1>(q, K, V, B, n, L, cap, H, scale, o, part, st);
         } else {
-            // head_dim 128 with two query blocks per wavefront does not fit the register file
+            // head_dim 128 with two query blocks per wavefront does not fit the register budget of
+            // two wavefronts per SIMD, which is what lets one wavefront's softmax overlap the
+            // other's MFMAs
             launch_attn_bf16<128, 1>(q, K, V, B, n, L, cap, H, scale, o, part, st);
         }
     } else {
