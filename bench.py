@@ -285,15 +285,17 @@ def variants(chain, W, fv, torch, steps):
             "cache_factors": fac}
 
 
-def cpu_baseline(W):
-    """The CPU oracle on a bounded sample: one block, one batch element, both late scales."""
+def cpu_baseline(W, scales=None):
+    """The CPU oracle on a bounded sample: one block, one batch element, the late scales (or the
+    given subset of them)."""
     import numpy as np
     import oracle
     import workloads as wl
     d, H, F, r = W.hidden, W.heads, W.ffn_hidden, W.rank
     w = oracle.BlockWeights(**wl.block_weights(d, F, seed=2000, bf16=True))
     tokens, secs = 0, 0.0
-    for side in W.late_scales:
+    scales = tuple(scales or W.late_scales)
+    for side in scales:
         M, k, Lp = W.tokens(side), W.keep(side), W.prev_len(side)
         x = wl.activations_lowrank(1, M, d, seed=1000 + side, bf16=True)[0]
         Kp, Vp = wl.kv_prefix(1, Lp, H, d // H, seed=3000, bf16=True)
@@ -309,7 +311,7 @@ def cpu_baseline(W):
     return {"value": tokens / (per_block_sample * W.blocks), "unit": "tokens/s",
             "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"1 of {W.blocks} blocks x 1 of {W.batch} samples, scales "
-                      f"{'+'.join(str(s) for s in W.late_scales)} ({secs:.2f} s measured); value = "
+                      f"{'+'.join(str(s) for s in scales)} ({secs:.2f} s measured); value = "
                       f"sample tokens / (sample time x {W.blocks} blocks), i.e. extrapolated to the "
                       "full depth"}
 
@@ -323,6 +325,9 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the random-projection input variant and the factor construction")
+    ap.add_argument("--workload", default=WORKLOAD, choices=None,
+                    help="another shape of workloads.WORKLOADS (default: the depth-30 512 px one "
+                         "the headline figure is quoted on)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB device copy (reference for scaling HBM counters)")
     args = ap.parse_args()
@@ -334,7 +339,12 @@ def main():
     import workloads as wl
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    W = wl.WORKLOADS[WORKLOAD]
+    if args.workload not in wl.WORKLOADS:
+        sys.exit(f"unknown workload {args.workload}; known: {', '.join(wl.WORKLOADS)}")
+    default_wl = args.workload == WORKLOAD
+    W = wl.WORKLOADS[args.workload]
+    if W.dtype != "bf16":
+        sys.exit("bench.py times the bf16 shapes; the fp32 shape is a parity configuration")
     chain = Chain(W, fv, torch)
 
     if args.calib_copy:
@@ -410,7 +420,8 @@ def main():
     achieved = g_flop / (g_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (qkv, o, fc1, fc2 launches)",
                 "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES,
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                "traffic": GEMM_TRAFFIC_BYTES if default_wl else None,
                 "avg_launch_us": round(g_ms * 1e3 / g_launch, 2),
                 "flop_per_launch": g_flop / g_launch,
                 "share_of_kernel_time": round(g_ms / total_ms, 3)}
@@ -421,7 +432,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": W.dtype,
         "data": "synthetic",
-        "config": {"workload": WORKLOAD, "hidden": W.hidden, "heads": W.heads,
+        "config": {"workload": args.workload, "hidden": W.hidden, "heads": W.heads,
                    "head_dim": W.head_dim, "blocks": W.blocks, "batch": W.batch,
                    "late_scales": list(W.late_scales), "keep_ratio": W.keep_num / W.keep_den,
                    "rank": W.rank, "kv_tokens": W.total_len()},
@@ -431,10 +442,11 @@ def main():
         "roofline": roofline,
         "kernels": report,
     }
-    if not args.no_variants:
+    if not args.no_variants and default_wl:
         out["variants"] = variants(chain, W, fv, torch, max(2, args.steps // 3))
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(W)
+        # the other shapes are larger: their sample is the first late scale only
+        out["cpu_baseline"] = cpu_baseline(W, None if default_wl else W.late_scales[:1])
     print(json.dumps(out))
 
 
