@@ -323,3 +323,21 @@ def test_block_chunk_with_one_selection(dtype, B, M, k, d, H, Lp, r, nblk):
         for i in range(nblk):
             assert rel_err(to_np(blks[i].K[b, Lp:]), caches[i][0][Lp:]) <= TOL[dtype]
             assert rel_err(to_np(blks[i].V[b, Lp:]), caches[i][1][Lp:]) <= TOL[dtype]
+
+
+def test_cache_factors_depth30_launch_shape():
+    # the shape the benchmark times (batch 8, scale 32, rank 64): two samples against the oracle
+    W = wl.WORKLOADS["var_d30_512_bf16"]
+    B, M, d, r = W.batch, W.tokens(32), W.hidden, W.rank
+    Cm = wl.round_to_bf16(wl.cached_feature(B, M, d, 180, seed=4100, noise=0.1))
+    Q = _q(B, M, r, 4101, "bf16", False)
+    ctx = _ctx(d, "bf16", H=W.heads)
+    w_c = torch.empty((B, M, r), dtype=torch.bfloat16, device="cuda")
+    g_c = torch.empty((B, r, d), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(fv.fvar_factors_workspace_bytes(ctx, B, M, r), dtype=torch.uint8, device="cuda")
+    fv.fvar_cache_factors(ctx, to_dev(Cm, "bf16"), _qt_dev(Q, "bf16"), False, B, M, r, 0.0, w_c, g_c, ws)
+    torch.cuda.synchronize()
+    for b in (0, 7):
+        Wo, Go = factors.stored_factors(Cm[b], Q[0], bf16=True)
+        assert rel_err(to_np(g_c[b]), Go) <= TOL["bf16"]
+        assert rel_err(to_np(w_c[b]), Wo) <= TOL["bf16"]
