@@ -285,9 +285,9 @@ def variants(chain, W, fv, torch, steps):
             "cache_factors": fac}
 
 
-def cpu_baseline(W, scales=None):
-    """The CPU oracle on a bounded sample: one block, one batch element, the late scales (or the
-    given subset of them)."""
+def cpu_baseline(W, scales=None, samples=1):
+    """The CPU oracle on a bounded sample: one block, `samples` batch elements, the late scales
+    (or the given subset of them); about 10 s of work on the host cores for the default workload."""
     import numpy as np
     import oracle
     import workloads as wl
@@ -295,22 +295,23 @@ def cpu_baseline(W, scales=None):
     w = oracle.BlockWeights(**wl.block_weights(d, F, seed=2000, bf16=True))
     tokens, secs = 0, 0.0
     scales = tuple(scales or W.late_scales)
+    samples = max(1, min(samples, W.batch))
     for side in scales:
         M, k, Lp = W.tokens(side), W.keep(side), W.prev_len(side)
-        x = wl.activations_lowrank(1, M, d, seed=1000 + side, bf16=True)[0]
-        Kp, Vp = wl.kv_prefix(1, Lp, H, d // H, seed=3000, bf16=True)
-        Wc, Gc = wl.direct_factors(1, M, r, d, seed=4000, bf16=True)
-        Kc = np.zeros((Lp + k, H, d // H), np.float32)
-        Vc = np.zeros_like(Kc)
-        Kc[:Lp], Vc[:Lp] = Kp[0], Vp[0]
-        t0 = time.perf_counter()
-        oracle.pruned_step(x, k, w, H, Kc, Vc, Lp, Wc[0], Gc[0])
-        secs += time.perf_counter() - t0
-        tokens += M
-    per_block_sample = secs
-    return {"value": tokens / (per_block_sample * W.blocks), "unit": "tokens/s",
+        x = wl.activations_lowrank(samples, M, d, seed=1000 + side, bf16=True)
+        Kp, Vp = wl.kv_prefix(samples, Lp, H, d // H, seed=3000, bf16=True)
+        Wc, Gc = wl.direct_factors(samples, M, r, d, seed=4000, bf16=True)
+        for b in range(samples):
+            Kc = np.zeros((Lp + k, H, d // H), np.float32)
+            Vc = np.zeros_like(Kc)
+            Kc[:Lp], Vc[:Lp] = Kp[b], Vp[b]
+            t0 = time.perf_counter()
+            oracle.pruned_step(x[b], k, w, H, Kc, Vc, Lp, Wc[b], Gc[b])
+            secs += time.perf_counter() - t0
+            tokens += M
+    return {"value": tokens / (secs * W.blocks), "unit": "tokens/s",
             "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"1 of {W.blocks} blocks x 1 of {W.batch} samples, scales "
+            "sample": f"1 of {W.blocks} blocks x {samples} of {W.batch} samples, scales "
                       f"{'+'.join(str(s) for s in scales)} ({secs:.2f} s measured); value = "
                       f"sample tokens / (sample time x {W.blocks} blocks), i.e. extrapolated to the "
                       "full depth"}
@@ -446,7 +447,8 @@ def main():
         out["variants"] = variants(chain, W, fv, torch, max(2, args.steps // 3))
     if not args.no_cpu_baseline:
         # the other shapes are larger: their sample is the first late scale only
-        out["cpu_baseline"] = cpu_baseline(W, None if default_wl else W.late_scales[:1])
+        out["cpu_baseline"] = (cpu_baseline(W, samples=W.batch) if default_wl
+                               else cpu_baseline(W, W.late_scales[:1]))
     print(json.dumps(out))
 
 
