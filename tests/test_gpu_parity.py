@@ -179,8 +179,9 @@ def test_dense_block_small_and_keep_all(dtype, B, M, d, H, F, Lp, k, r):
     assert torch.equal(blk2.K, blk.K) and torch.equal(blk2.V, blk.V)
 
 
-def test_runs_are_deterministic():
-    dtype, B, M, d, H, F, Lp, k, r = SMALL[1]
+@pytest.mark.parametrize("case", [1, 9, 11])     # plain; key axis of the attention split; linear layers split along k
+def test_runs_are_deterministic(case):
+    dtype, B, M, d, H, F, Lp, k, r = SMALL[case]
     x, w, Kp, Vp, Wc, Gc = make_case(dtype, B, M, d, H, F, Lp, r, seed=7)
     outs = []
     for _ in range(2):
