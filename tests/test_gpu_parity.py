@@ -285,3 +285,36 @@ def test_head_dim_128_workloads_real_shape(name, side, B):
     for b in range(B):
         assert np.array_equal(yg[b][kk[b]], to_np(y_keep[b]))
         assert rel_err(yg[b][dd[b]], ref["y"][b][dd[b]]) <= 2e-2
+
+
+# ----------------------------------------------------------------------------- random geometry
+@pytest.mark.parametrize("seed", range(12))
+def test_pruned_path_random_geometry(seed):
+    """Seeded random geometry inside the documented limits (head_dim 64 or 128, 1-4 heads, ragged
+    token counts, cache prefixes around the 64-key tile edges, any keep count): same bar."""
+    rng = np.random.default_rng(5000 + seed)
+    dtype = "bf16" if seed % 4 else "f32"
+    Dh, H = int(rng.choice([64, 128])), int(rng.integers(1, 5))
+    d = H * Dh
+    F = int(rng.choice([64, 128, 192, 256, 512])) * int(rng.integers(1, 4))
+    r = int(rng.choice([4, 8, 12, 32])) if dtype == "f32" else int(rng.choice([8, 16, 24, 64]))
+    B, M = int(rng.integers(1, 4)), max(r, int(rng.integers(1, 400)))
+    k = int(rng.integers(1, M + 1))
+    Lp = int(rng.choice([0, 1, 63, 64, 65, 200, 700, 1300]))
+    x, w, Kp, Vp, Wc, Gc = make_case(dtype, B, M, d, H, F, Lp, r, seed=6000 + seed,
+                                     bias=bool(seed & 1), affine=bool(seed & 2))
+    ref = oracle_pruned(x, k, w, H, Kp, Vp, Wc, Gc)
+    blk = GpuBlock(d, H, F, dtype, w, Kp, Vp, Lp + M)
+    xd = to_dev(x, dtype)
+    s, keep, drop = blk.score_select(xd, k)
+    y_keep = blk.pruned(xd, keep, k)
+    y = blk.fill(y_keep, keep, drop, M, to_dev(Wc, dtype), to_dev(Gc, dtype))
+    torch.cuda.synchronize()
+    same_scores_or_xfail(s, keep, drop, x, k, ref)
+    assert np.array_equal(keep.cpu().numpy(), ref["idx_keep"])
+    assert np.array_equal(drop.cpu().numpy(), ref["idx_drop"])
+    tol = TOL[dtype]
+    assert rel_err(to_np(blk.K[:, Lp:Lp + k]), ref["K_new"]) <= tol
+    assert rel_err(to_np(blk.V[:, Lp:Lp + k]), ref["V_new"]) <= tol
+    assert rel_err(to_np(y_keep), ref["y_keep"]) <= tol
+    assert rel_err(to_np(y), ref["y"]) <= tol
