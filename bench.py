@@ -329,6 +329,9 @@ def main():
     ap.add_argument("--workload", default=WORKLOAD, choices=None,
                     help="another shape of workloads.WORKLOADS (default: the depth-30 512 px one "
                          "the headline figure is quoted on)")
+    ap.add_argument("--keep", default=None, metavar="NUM/DEN",
+                    help="keep ratio instead of the workload's (e.g. 3/10); 1/1 runs every row")
+    ap.add_argument("--rank", type=int, default=None, help="fill rank instead of the workload's")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB device copy (reference for scaling HBM counters)")
     args = ap.parse_args()
@@ -346,6 +349,11 @@ def main():
     W = wl.WORKLOADS[args.workload]
     if W.dtype != "bf16":
         sys.exit("bench.py times the bf16 shapes; the fp32 shape is a parity configuration")
+    if args.keep or args.rank:
+        import dataclasses
+        num, den = (int(t) for t in args.keep.split("/")) if args.keep else (W.keep_num, W.keep_den)
+        W = dataclasses.replace(W, keep_num=num, keep_den=den, rank=args.rank or W.rank)
+        default_wl = False
     chain = Chain(W, fv, torch)
 
     if args.calib_copy:
