@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the late-scale pruned block path on one MI355X.
 
-A step = both late scales of the VAR-d30-shaped 512 px workload (24x24 and 32x32 tokens, batch 8,
-hidden 1920, 30 heads) through all 30 blocks; every block runs score -> select -> pruned block
-(gather, LN, QKV, attention over the multi-scale cache, O, LN, MLP) -> low-rank fill + scatter,
-and its output token map is the next block's input.  Inputs are synthetic and resident in HBM.
-Prints one JSON line."""
+A step = every late scale of the workload through all of its blocks; every block runs score ->
+select -> pruned block (gather, LN, QKV, attention over the multi-scale cache, O, LN, MLP) ->
+low-rank fill + scatter, and its output token map is the next block's input.  The default
+workload is the largest single-GPU shape: hidden 4096, 32 heads of 128, 40 blocks, the 80x80
+scale (6400 tokens, 1600 kept, 12121 keys), rank 128, batch 4; `--workload` selects the other
+shapes and `--sweep` runs the keep-ratio x rank x scale table of the batch-32 Infinity-2B shape.
+Inputs are synthetic and resident in HBM.  Prints one JSON line."""
 from __future__ import annotations
 
 import argparse
@@ -20,11 +22,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
-WORKLOAD = "var_d30_512_bf16"
-# HBM-side bytes per GEMM launch (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size;
-# profiles/pruned_chain_var_d30_512_hbm_counters.txt).  Set to None whenever gemm.hip changes
-# until the counters are taken again.
-GEMM_TRAFFIC_BYTES = 166.9e6
+WORKLOAD = "large_1280_bf16"
+# HBM-side bytes per GEMM launch of a workload (FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs,
+# each scaled by what the same counter reads for a device copy of known size; the summary file
+# under profiles/ is named in the entry).  An entry is dropped (traffic: null) whenever gemm.hip
+# changes, until the counters are taken again.
+GEMM_TRAFFIC = {}
+SWEEP_WORKLOAD = "infinity2b_1024_b32_bf16"
 
 
 class Chain:
@@ -37,6 +41,13 @@ class Chain:
                               ffn_hidden=W.ffn_hidden, scales=W.scales, dtype=W.dtype)
         self.blocks = wl.device_block_state(W)
         self.cap = W.total_len()
+        self.set_reduction(W)
+
+    def set_reduction(self, W):
+        """(Re)build the per-scale state for W's keep ratio and rank; weights and caches stay."""
+        import workloads as wl
+        fv, torch = self.fv, self.torch
+        self.W = W
         self.scale = {}
         dt = torch.bfloat16 if W.dtype == "bf16" else torch.float32
         B, d = W.batch, W.hidden
@@ -285,102 +296,69 @@ def variants(chain, W, fv, torch, steps):
             "cache_factors": fac}
 
 
-def cpu_baseline(W, scales=None, samples=1):
+def cpu_baseline(W, scales=None, samples=1, budget_gflop=300.0):
     """The CPU oracle on a bounded sample: one block, `samples` batch elements, the late scales
-    (or the given subset of them); about 10 s of work on the host cores for the default workload."""
+    (or the given subset of them).  When one sample's pruned step exceeds `budget_gflop` (about
+    20 s on the host cores) the oracle runs with a quarter (or a sixteenth ...) of the kept rows
+    and the time is scaled back up: all but a few per cent of the oracle's work is per kept row."""
     import numpy as np
     import oracle
     import workloads as wl
     d, H, F, r = W.hidden, W.heads, W.ffn_hidden, W.rank
     w = oracle.BlockWeights(**wl.block_weights(d, F, seed=2000, bf16=True))
-    tokens, secs = 0, 0.0
+    tokens, secs, notes = 0, 0.0, []
     scales = tuple(scales or W.late_scales)
     samples = max(1, min(samples, W.batch))
     for side in scales:
         M, k, Lp = W.tokens(side), W.keep(side), W.prev_len(side)
+        div = 1
+        while (24.0 * d * d + 4.0 * (Lp + k) * d) * (k / div) > budget_gflop * 1e9 and k // (div * 4) >= 1:
+            div *= 4
+        ks = max(1, k // div)
+        if div > 1:
+            notes.append(f"scale {side}: oracle run with {ks} of the {k} kept rows, time x {k / ks:.3g}")
         x = wl.activations_lowrank(samples, M, d, seed=1000 + side, bf16=True)
         Kp, Vp = wl.kv_prefix(samples, Lp, H, d // H, seed=3000, bf16=True)
         Wc, Gc = wl.direct_factors(samples, M, r, d, seed=4000, bf16=True)
         for b in range(samples):
-            Kc = np.zeros((Lp + k, H, d // H), np.float32)
+            Kc = np.zeros((Lp + ks, H, d // H), np.float32)
             Vc = np.zeros_like(Kc)
             Kc[:Lp], Vc[:Lp] = Kp[b], Vp[b]
             t0 = time.perf_counter()
-            oracle.pruned_step(x[b], k, w, H, Kc, Vc, Lp, Wc[b], Gc[b])
-            secs += time.perf_counter() - t0
+            oracle.pruned_step(x[b], ks, w, H, Kc, Vc, Lp, Wc[b], Gc[b])
+            secs += (time.perf_counter() - t0) * (k / ks)
             tokens += M
     return {"value": tokens / (secs * W.blocks), "unit": "tokens/s",
             "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"1 of {W.blocks} blocks x {samples} of {W.batch} samples, scales "
-                      f"{'+'.join(str(s) for s in scales)} ({secs:.2f} s measured); value = "
-                      f"sample tokens / (sample time x {W.blocks} blocks), i.e. extrapolated to the "
-                      "full depth"}
+                      f"{'+'.join(str(s) for s in scales)} ({secs:.2f} s"
+                      f"{' after scaling' if notes else ' measured'}); value = sample tokens / "
+                      f"(sample time x {W.blocks} blocks), i.e. extrapolated to the full depth"
+                      + ("; " + "; ".join(notes) if notes else "")}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--no-variants", action="store_true",
-                    help="skip the random-projection input variant and the factor construction")
-    ap.add_argument("--workload", default=WORKLOAD, choices=None,
-                    help="another shape of workloads.WORKLOADS (default: the depth-30 512 px one "
-                         "the headline figure is quoted on)")
-    ap.add_argument("--keep", default=None, metavar="NUM/DEN",
-                    help="keep ratio instead of the workload's (e.g. 3/10); 1/1 runs every row")
-    ap.add_argument("--rank", type=int, default=None, help="fill rank instead of the workload's")
-    ap.add_argument("--calib-copy", action="store_true",
-                    help="also run one 256 MiB device copy (reference for scaling HBM counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py measures one GPU: this path has no multi-GPU part (run with --gpus 1)")
-
-    import torch
-    import paper_2512_16483_amd as fv
-    import workloads as wl
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    if args.workload not in wl.WORKLOADS:
-        sys.exit(f"unknown workload {args.workload}; known: {', '.join(wl.WORKLOADS)}")
-    default_wl = args.workload == WORKLOAD
-    W = wl.WORKLOADS[args.workload]
-    if W.dtype != "bf16":
-        sys.exit("bench.py times the bf16 shapes; the fp32 shape is a parity configuration")
-    if args.keep or args.rank:
-        import dataclasses
-        num, den = (int(t) for t in args.keep.split("/")) if args.keep else (W.keep_num, W.keep_den)
-        W = dataclasses.replace(W, keep_num=num, keep_den=den, rank=args.rank or W.rank)
-        default_wl = False
-    chain = Chain(W, fv, torch)
-
-    if args.calib_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-    for _ in range(args.warmup):
+def measure(chain, W, fv, torch, steps, warmup, with_dense=True, dense_steps=None):
+    """Times `steps` steps of the pruned chain (and the dense control), then reads the per-kernel
+    durations of one more pass.  Returns the pieces of the JSON line."""
+    for _ in range(warmup):
         chain.step()
     torch.cuda.synchronize()
     events = {}
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         chain.step(events=events)
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
     tokens = W.batch * sum(W.tokens(s) for s in W.late_scales)
     ms_scale = {str(s): sum(a.elapsed_time(b) for a, b in ev) / len(ev) for s, ev in events.items()}
 
     # dense control, same chain without the reduction
     dense = None
-    if not args.no_dense:
+    if with_dense:
         chain.step(dense=True)
         torch.cuda.synchronize()
         dev = {}
-        n = max(2, args.steps // 3)
+        n = dense_steps or max(2, steps // 3)
         t0 = time.perf_counter()
         for _ in range(n):
             chain.step(dense=True, events=dev)
@@ -429,11 +407,109 @@ def main():
     achieved = g_flop / (g_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel (qkv, o, fc1, fc2 launches)",
                 "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": GEMM_TRAFFIC_BYTES if default_wl else None,
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                 "avg_launch_us": round(g_ms * 1e3 / g_launch, 2),
                 "flop_per_launch": g_flop / g_launch,
                 "share_of_kernel_time": round(g_ms / total_ms, 3)}
+    return {"ms_per_step": ms_per_step, "tokens": tokens, "ms_per_scale": ms_scale, "dense": dense,
+            "roofline": roofline, "kernels": report}
+
+
+def sweep(fv, torch, wl, steps, warmup):
+    """Keep ratio {1, 1/2, 3/10, 1/5} x rank {16, 64, 128} on the late scales {40, 48, 64} of the
+    Infinity-2B shape at batch 16 x 2, the dense chain as control: one row per combination with the
+    time per late scale.  The rank only enters the fill, so the ranks other than the workload's
+    own are timed at the workload's keep ratio."""
+    import dataclasses
+    W0 = wl.WORKLOADS[SWEEP_WORKLOAD]
+    chain = Chain(W0, fv, torch)
+    rows, dense = [], None
+    combos = [(1, 1, W0.rank), (1, 2, W0.rank), (3, 10, W0.rank), (1, 5, W0.rank), (3, 10, 16), (3, 10, 128)]
+    for num, den, r in combos:
+        W = dataclasses.replace(W0, keep_num=num, keep_den=den, rank=r)
+        chain.set_reduction(W)
+        m = measure(chain, W, fv, torch, steps, warmup, with_dense=dense is None, dense_steps=2)
+        dense = dense or m["dense"]
+        rows.append({"keep": f"{num}/{den}", "rank": r,
+                     "k": {str(s): W.keep(s) for s in W.late_scales},
+                     "ms_per_step": round(m["ms_per_step"], 2),
+                     "ms_per_scale": {k: round(v, 2) for k, v in m["ms_per_scale"].items()},
+                     "speedup_vs_dense": round(dense["ms_per_step"] / m["ms_per_step"], 3),
+                     "tokens_per_s": m["tokens"] / (m["ms_per_step"] * 1e-3),
+                     "gemm_frac_of_mfma_peak": m["roofline"]["frac"],
+                     "attention": m["kernels"].get("attention"), "fill": m["kernels"].get("fill"),
+                     "score": m["kernels"].get("score")})
+    return W0, rows, dense
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the random-projection input variant and the factor construction")
+    ap.add_argument("--workload", default=WORKLOAD, choices=None,
+                    help="another shape of workloads.WORKLOADS (default: the largest one, hidden "
+                         "4096 at the 80x80 scale, which the headline figure is quoted on)")
+    ap.add_argument("--keep", default=None, metavar="NUM/DEN",
+                    help="keep ratio instead of the workload's (e.g. 3/10); 1/1 runs every row")
+    ap.add_argument("--rank", type=int, default=None, help="fill rank instead of the workload's")
+    ap.add_argument("--sweep", action="store_true",
+                    help=f"keep-ratio x rank x scale table of {SWEEP_WORKLOAD} instead of one workload")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 256 MiB device copy (reference for scaling HBM counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this path has no multi-GPU part (run with --gpus 1)")
+
+    import torch
+    import paper_2512_16483_amd as fv
+    import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    if args.sweep:
+        W, rows, dense = sweep(fv, torch, wl, max(2, args.steps // 3), max(1, args.warmup // 2))
+        ref = next(r for r in rows if r["keep"] == f"{W.keep_num}/{W.keep_den}" and r["rank"] == W.rank)
+        print(json.dumps({
+            "metric": "late-scale pruned block throughput (tokens/s; ms per late scale in ms_per_scale)",
+            "value": ref["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": max(2, args.steps // 3),
+            "warmup": max(1, args.warmup // 2), "ms_per_step": ref["ms_per_step"],
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": W.dtype,
+            "data": "synthetic",
+            "config": {"workload": SWEEP_WORKLOAD + " (keep x rank sweep)", "hidden": W.hidden,
+                       "heads": W.heads, "head_dim": W.head_dim, "blocks": W.blocks, "batch": W.batch,
+                       "late_scales": list(W.late_scales), "kv_tokens": W.total_len()},
+            "dense_control": dense, "sweep": rows}))
+        return
+
+    if args.workload not in wl.WORKLOADS:
+        sys.exit(f"unknown workload {args.workload}; known: {', '.join(wl.WORKLOADS)}")
+    default_wl = args.workload == WORKLOAD
+    W = wl.WORKLOADS[args.workload]
+    if W.dtype != "bf16":
+        sys.exit("bench.py times the bf16 shapes; the fp32 shape is a parity configuration")
+    if args.keep or args.rank:
+        import dataclasses
+        num, den = (int(t) for t in args.keep.split("/")) if args.keep else (W.keep_num, W.keep_den)
+        W = dataclasses.replace(W, keep_num=num, keep_den=den, rank=args.rank or W.rank)
+        default_wl = False
+    chain = Chain(W, fv, torch)
+
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+    m = measure(chain, W, fv, torch, args.steps, args.warmup, with_dense=not args.no_dense)
+    ms_per_step, tokens, dense = m["ms_per_step"], m["tokens"], m["dense"]
+    traffic = GEMM_TRAFFIC.get(args.workload) if not (args.keep or args.rank) else None
+    if traffic:
+        m["roofline"]["traffic"] = traffic["bytes_per_launch"]
+        m["roofline"]["traffic_source"] = traffic["source"]
 
     out = {
         "metric": "late-scale pruned block throughput (tokens/s; ms per late scale in ms_per_scale)",
@@ -445,18 +521,17 @@ def main():
                    "head_dim": W.head_dim, "blocks": W.blocks, "batch": W.batch,
                    "late_scales": list(W.late_scales), "keep_ratio": W.keep_num / W.keep_den,
                    "rank": W.rank, "kv_tokens": W.total_len()},
-        "ms_per_scale": ms_scale,
+        "ms_per_scale": m["ms_per_scale"],
         "dense_control": dense,
         "speedup_vs_dense": (dense["ms_per_step"] / ms_per_step) if dense else None,
-        "roofline": roofline,
-        "kernels": report,
+        "roofline": m["roofline"],
+        "kernels": m["kernels"],
     }
     if not args.no_variants and default_wl:
         out["variants"] = variants(chain, W, fv, torch, max(2, args.steps // 3))
     if not args.no_cpu_baseline:
-        # the other shapes are larger: their sample is the first late scale only
-        out["cpu_baseline"] = (cpu_baseline(W, samples=W.batch) if default_wl
-                               else cpu_baseline(W, W.late_scales[:1]))
+        # bounded sample: one block, one sample, the first late scale
+        out["cpu_baseline"] = cpu_baseline(W, W.late_scales[:1])
     print(json.dumps(out))
 
 

@@ -32,12 +32,23 @@
  *    calls only enqueue work on it and return without synchronising.  The
  *    returned status covers argument validation and launch errors, not kernel
  *    completion.
- *  - On any error nothing has been launched; fvar_last_error() returns a text
- *    for the last failing call on that context.
- *  - A context may be used from one thread at a time.  No global state.
+ *  - Arguments are validated before anything is enqueued: FVAR_ERR_INVALID_ARG,
+ *    FVAR_ERR_UNSUPPORTED and FVAR_ERR_WORKSPACE mean that nothing has been
+ *    launched.  FVAR_ERR_HIP reports a failed runtime call or kernel launch and
+ *    may come after earlier kernels of the same call were enqueued; the outputs
+ *    are then undefined.  fvar_last_error() returns a text for the last failing
+ *    call on that context.
+ *  - A context may be used from one thread at a time.  State outside a context:
+ *    a thread-local pointer that exists only while a call with per-kernel
+ *    timing switched on is enqueueing its kernels.
  *  - Index arrays are int32, strictly ascending per sample and in range; this is
- *    the caller's contract for fvar_block_forward_pruned / fvar_lowrank_fill
- *    (fvar_score_select produces arrays that satisfy it).
+ *    the caller's contract for fvar_block_forward_pruned / fvar_lowrank_fill /
+ *    fvar_cache_fill (fvar_score_select produces arrays that satisfy it).
+ *    fvar_debug_checks() makes the library verify it.
+ *  - Size limits of the block calls: B*rows <= 2^24, B <= 8191, and every operand
+ *    matrix (B*rows x max(hidden, ffn_hidden) elements) below 4 GiB, because the
+ *    linear-layer kernels use 32-bit byte offsets inside a matrix; larger calls
+ *    return FVAR_ERR_UNSUPPORTED.
  */
 #ifndef FVAR_H
 #define FVAR_H
@@ -216,6 +227,15 @@ fvar_status fvar_cache_factors(fvar_ctx *ctx, fvar_stream stream, const void *ca
 fvar_status fvar_upsample_tokens(fvar_ctx *ctx, fvar_stream stream, const void *src, int32_t B,
                                  int32_t hs, int32_t ws, int32_t c, int32_t hd, int32_t wd,
                                  void *dst);
+
+/* Debug checks, off by default.  While on, fvar_block_forward_pruned, fvar_lowrank_fill and
+ * fvar_cache_fill copy their index arrays to the host and verify the contract (in range,
+ * strictly ascending per sample, idx_keep and idx_drop disjoint, hence a partition of [0,M));
+ * a violation returns FVAR_ERR_INVALID_ARG with nothing launched.  The block calls also put a
+ * 256-byte canary behind their workspace (fvar_block_workspace_bytes grows by that much while
+ * the checks are on) and return FVAR_ERR_WORKSPACE if a kernel overwrote it.  Calls made with
+ * the checks on synchronise the stream and are not asynchronous. */
+fvar_status fvar_debug_checks(fvar_ctx *ctx, int32_t on);
 
 /* Per-kernel timing (hipEvent pairs around every launch while enabled).  Off by default and
  * outside any throughput measurement.  fvar_profile_read synchronises the recorded events,

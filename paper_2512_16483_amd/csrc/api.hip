@@ -20,6 +20,7 @@ struct fvar_ctx {
     std::vector<int32_t> scale_hw;
     float eps, scale;
     char err[256];
+    bool debug_checks = false;
     // per-kernel timing
     bool profiling = false;
     struct Rec { std::string label; hipEvent_t a, b; };
@@ -75,6 +76,62 @@ fvar_status launch_status(fvar_ctx *c, const char *what)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, FVAR_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
     c->err[0] = 0;
+    return FVAR_OK;
+}
+
+constexpr size_t kCanaryBytes = 256;
+constexpr unsigned char kCanaryByte = 0xA5;
+
+// Debug checks: the index arrays are the caller's contract in normal operation; with the checks
+// switched on they are brought to the host (which synchronises the stream) and verified:
+// in range, strictly ascending per sample, and -- when both lists are given -- together exactly
+// the set [0, M).
+fvar_status validate_indices(fvar_ctx *c, hipStream_t st, const int32_t *idx_keep,
+                             const int32_t *idx_drop, int B, int M, int k, const char *who)
+{
+    if (hipStreamSynchronize(st) != hipSuccess)
+        return fail(c, FVAR_ERR_HIP, "%s: stream synchronisation failed in the index check", who);
+    std::vector<int32_t> hk, hd;
+    if (idx_keep && k > 0) {
+        hk.resize((size_t)B * k);
+        if (hipMemcpy(hk.data(), idx_keep, hk.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+            return fail(c, FVAR_ERR_HIP, "%s: cannot read idx_keep", who);
+    }
+    if (idx_drop && k < M) {
+        hd.resize((size_t)B * (M - k));
+        if (hipMemcpy(hd.data(), idx_drop, hd.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+            return fail(c, FVAR_ERR_HIP, "%s: cannot read idx_drop", who);
+    }
+    auto ascending = [&](const int32_t *v, int n, const char *name, int b) -> bool {
+        for (int j = 0; j < n; ++j) {
+            if (v[j] < 0 || v[j] >= M) {
+                fail(c, FVAR_ERR_INVALID_ARG, "%s: %s[%d,%d] = %d is outside [0,%d)", who, name, b, j, v[j], M);
+                return false;
+            }
+            if (j > 0 && v[j] <= v[j - 1]) {
+                fail(c, FVAR_ERR_INVALID_ARG, "%s: %s[%d,:] is not strictly ascending at position %d", who,
+                     name, b, j);
+                return false;
+            }
+        }
+        return true;
+    };
+    for (int b = 0; b < B; ++b) {
+        const int32_t *kp = hk.empty() ? nullptr : hk.data() + (size_t)b * k;
+        const int32_t *dp = hd.empty() ? nullptr : hd.data() + (size_t)b * (M - k);
+        if (kp && !ascending(kp, k, "idx_keep", b)) return FVAR_ERR_INVALID_ARG;
+        if (dp && !ascending(dp, M - k, "idx_drop", b)) return FVAR_ERR_INVALID_ARG;
+        if (kp && dp) {
+            // two ascending in-range lists of k and M-k entries partition [0,M) iff they share no entry
+            int i = 0, j = 0;
+            while (i < k && j < M - k) {
+                if (kp[i] == dp[j])
+                    return fail(c, FVAR_ERR_INVALID_ARG, "%s: token %d of sample %d is in idx_keep and idx_drop",
+                                who, kp[i], b);
+                if (kp[i] < dp[j]) ++i; else ++j;
+            }
+        }
+    }
     return FVAR_OK;
 }
 
@@ -135,10 +192,34 @@ fvar_status block_forward(fvar_ctx *c, hipStream_t st, const fvar_block_weights 
         if (!aligned16(p)) return fail(c, FVAR_ERR_INVALID_ARG, "%s: pointer not 16-byte aligned", who);
     if ((int64_t)B * rows > (1 << 24))
         return fail(c, FVAR_ERR_UNSUPPORTED, "%s: B*rows exceeds 2^24", who);
+    {
+        // the linear-layer kernels address their operand tiles with 32-bit byte offsets from the
+        // matrix base, and the attention grid carries (sample, key range) in blockIdx.z
+        const int64_t wide = c->cfg.hidden > c->cfg.ffn_hidden ? c->cfg.hidden : c->cfg.ffn_hidden;
+        const int64_t es = (int64_t)esize(c);
+        if ((int64_t)B * rows * wide * es >= ((int64_t)1 << 32) ||
+            (int64_t)3 * c->cfg.hidden * c->cfg.hidden * es >= ((int64_t)1 << 32) ||
+            (int64_t)c->cfg.ffn_hidden * c->cfg.hidden * es >= ((int64_t)1 << 32))
+            return fail(c, FVAR_ERR_UNSUPPORTED,
+                        "%s: an operand matrix of B*rows=%lld rows reaches 4 GiB (32-bit tile offsets)",
+                        who, (long long)B * rows);
+        if ((int64_t)B * 8 > 65535 || c->cfg.heads > 65535)
+            return fail(c, FVAR_ERR_UNSUPPORTED, "%s: B or heads exceeds the launch grid limits", who);
+    }
     BlockWs s = carve(c, ws, B, rows);
-    if (!ws || ws_bytes < s.total)
-        return fail(c, FVAR_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, s.total,
+    const size_t ws_need = s.total + (c->debug_checks ? kCanaryBytes : 0);
+    if (!ws || ws_bytes < ws_need)
+        return fail(c, FVAR_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, ws_need,
                     ws_bytes);
+    if (c->debug_checks) {
+        if (idx) {
+            const fvar_status vs = validate_indices(c, st, idx, nullptr, B, M, rows, who);
+            if (vs != FVAR_OK) return vs;
+        }
+        // canary behind the carved workspace, verified after the kernels have finished
+        if (hipMemsetAsync(static_cast<char *>(ws) + s.total, kCanaryByte, kCanaryBytes, st) != hipSuccess)
+            return fail(c, FVAR_ERR_HIP, "%s: cannot write the workspace canary", who);
+    }
 
     const DType dt = dtype(c);
     const int d = c->cfg.hidden, H = c->cfg.heads, Dh = c->cfg.head_dim, F = c->cfg.ffn_hidden;
@@ -188,7 +269,17 @@ fvar_status block_forward(fvar_ctx *c, hipStream_t st, const fvar_block_weights 
         e.splitk_scratch = reinterpret_cast<float *>(s.gemm_part);
         fvar::launch_gemm(dt, s.hid, w->w_fc2, R, d, F, e, st);
     });
-    return launch_status(c, who);
+    const fvar_status ls = launch_status(c, who);
+    if (ls != FVAR_OK || !c->debug_checks) return ls;
+    unsigned char canary[kCanaryBytes];
+    if (hipStreamSynchronize(st) != hipSuccess ||
+        hipMemcpy(canary, static_cast<char *>(ws) + s.total, kCanaryBytes, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(c, FVAR_ERR_HIP, "%s: kernels failed (seen at the debug-check synchronisation)", who);
+    for (size_t i = 0; i < kCanaryBytes; ++i)
+        if (canary[i] != kCanaryByte)
+            return fail(c, FVAR_ERR_WORKSPACE, "%s: a kernel wrote past the end of its workspace (canary byte %zu)",
+                        who, i);
+    return FVAR_OK;
 }
 
 }  // namespace
@@ -276,7 +367,14 @@ size_t fvar_select_workspace_bytes(const fvar_ctx *c, int32_t B, int32_t M)
 size_t fvar_block_workspace_bytes(const fvar_ctx *c, int32_t B, int32_t rows)
 {
     if (!c || B < 1 || rows < 1) return 0;
-    return carve(c, nullptr, B, rows).total;
+    return carve(c, nullptr, B, rows).total + (c->debug_checks ? kCanaryBytes : 0);
+}
+
+fvar_status fvar_debug_checks(fvar_ctx *c, int32_t on)
+{
+    if (!c) return FVAR_ERR_INVALID_ARG;
+    c->debug_checks = on != 0;
+    return FVAR_OK;
 }
 
 fvar_status fvar_score_select(fvar_ctx *c, fvar_stream stream, const void *x, int32_t B, int32_t M,
@@ -354,6 +452,10 @@ fvar_status fvar_lowrank_fill(fvar_ctx *c, fvar_stream stream, const void *y_kee
     if (!aligned16(y) || !aligned16(y_keep) || !aligned16(w_c) || !aligned16(g_c))
         return fail(c, FVAR_ERR_INVALID_ARG, "%s: pointer not 16-byte aligned", who);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (c->debug_checks && k < M) {
+        const fvar_status vs = validate_indices(c, st, idx_keep, idx_drop, B, M, k, who);
+        if (vs != FVAR_OK) return vs;
+    }
     timed(c, st, "fill", [&] {
         fvar::launch_fill(dtype(c), y_keep, idx_keep, idx_drop, B, M, k, r, c->cfg.hidden, w_c, g_c, y,
                           st);
@@ -402,6 +504,10 @@ fvar_status fvar_cache_fill(fvar_ctx *c, fvar_stream stream, const void *y_keep,
     if ((int64_t)B * M > (int64_t)INT32_MAX / 2)
         return fail(c, FVAR_ERR_UNSUPPORTED, "%s: B*M too large", who);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (c->debug_checks) {
+        const fvar_status vs = validate_indices(c, st, idx_keep, idx_drop, B, M, k, who);
+        if (vs != FVAR_OK) return vs;
+    }
     timed(c, st, "cache_fill", [&] {
         fvar::launch_cache_fill(dtype(c), y_keep, idx_keep, idx_drop, B, M, k, c->cfg.hidden, cache, y,
                                 st);

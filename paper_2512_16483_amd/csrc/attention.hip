@@ -419,9 +419,6 @@ int attention_max_splits(DType dt, int B, int n, int H, int Dh)
     if (dt != DType::BF16) return 1;
     const bool wide = Dh == 64 && ((n % 256 == 0) || (n % 256 > 128));
     const long wgs = (long)((n + (wide ? 255 : 127)) / (wide ? 256 : 128)) * H * B;
-#ifdef FVAR_ATTN_SPLIT_OVERRIDE
-    if (FVAR_ATTN_SPLIT_OVERRIDE > 0) return FVAR_ATTN_SPLIT_OVERRIDE;      // tuning harness only
-#endif
     int best = 1;
     double best_cost = 1e300;
     const double per_split = wgs >= 256 ? 0.12 : 0.08;
@@ -440,12 +437,9 @@ static void launch_attn_bf16(const void *q, const void *K, const void *V, int B,
     constexpr int BQ = 128 * NQ;
     const size_t lds = (size_t)2 * 2 * BT * DH * sizeof(uint16_t);
     auto kern = attn_bf16_kernel<DH, NQ>;
-    static bool attr_set = false;
-    if (!attr_set && lds > 48 * 1024) {
+    if (lds > 48 * 1024)
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_set = true;
-    }
     // key ranges: every range at least 4 tiles long, none empty
     const int ntiles = (L + BT - 1) / BT;
     int nsplit = part ? attention_max_splits(DType::BF16, B, n, H, DH) : 1;

@@ -424,18 +424,12 @@ static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, 
     const size_t lds_epi = gemm_epi_lds_bytes(BM, BN, WM, WN, KS);
     const size_t lds = lds_stages > lds_epi ? lds_stages : lds_epi;
     auto kern = gemm_bf16_kernel<BM, BN, WM, WN, STAGES, KS>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_set = true;
-    }
+    // set on every launch: the attribute belongs to the current device's copy of the kernel
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     // patch height that minimises what one XCD has to pull through its own L2: a patch of g x c
     // tiles reads g row strips (BM x K) and c column strips (BN x K), with g * c = tiles / 8
     int group_m = (int)lround(sqrt((double)ntiles * BN / (8.0 * BM)));
-#ifdef FVAR_GROUP_M_OVERRIDE
-    if (FVAR_GROUP_M_OVERRIDE > 0) group_m = FVAR_GROUP_M_OVERRIDE;      // tuning harness only
-#endif
     group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
     launch(kern, dim3(grid), dim3(64 * WM * WN * KS), lds, st, (const uint16_t *)A,
                        (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, group_m, ep, nsplit, part);

@@ -119,6 +119,56 @@ def oracle_dense(x, weights, H, Kp, Vp):
     return np.stack(ys), np.stack(Kn), np.stack(Vn)
 
 
+def report(name: str, **errs) -> None:
+    """Print the observed errors of one case (visible with pytest -s / in the captured output of a
+    failing test) so that the margin to the bar can be read from the log."""
+    print(f"[parity] {name}: " + "  ".join(f"{k}={v:.4g}" for k, v in errs.items()), flush=True)
+
+
+def check_map(tag: str, y: np.ndarray, y_keep: np.ndarray, idx_keep: np.ndarray, idx_drop: np.ndarray,
+              ref_y: np.ndarray, tol: float, whole: bool = True) -> None:
+    """The scattered token map y:[M,d] of one sample against the oracle's.
+
+    The map holds two quantities: the block's output rows (copied from y_keep, which is compared
+    with the oracle under its own norm by the caller) and the restored rows W_c G_c.  The bar is
+    applied to each of them as a tensor of its own: kept rows must be the rows of y_keep bit for
+    bit (the scatter is a copy), restored rows must meet `tol` against the oracle's restored rows.
+    `whole` additionally holds the map as one tensor to `tol` (one rms floor over both kinds of
+    rows); it is switched off only for the 4096-hidden shape, whose kept rows alone sit at 0.7 of
+    the bar and are 1.5 times larger than the map's rms."""
+    assert np.array_equal(y[idx_keep], y_keep), f"{tag}: kept rows of the map differ from y_keep"
+    e_drop = rel_err(y[idx_drop], ref_y[idx_drop]) if idx_drop.size else 0.0
+    e_map = rel_err(y, ref_y)
+    report(f"{tag} map", restored_rows=e_drop, whole_map=e_map)
+    assert e_drop <= tol, (tag, "restored rows", e_drop)
+    if whole:
+        assert e_map <= tol, (tag, "whole map", e_map)
+
+
+def gpu_scores_identical(x: np.ndarray, dtype: str) -> bool:
+    """True when the scores the GPU stores for x:[B,M,d] equal the oracle's bit for bit.  The two
+    sides add the exact squares in a different order inside a double, so about one row in 1e7
+    lands on the other side of an fp32 rounding boundary; such a draw cannot be compared
+    element-wise downstream of the selection and the caller takes the next seed."""
+    B, M, d = x.shape
+    ctx = fv.Context(hidden=d, heads=d // 64, head_dim=64, ffn_hidden=64, dtype=dtype)
+    s = torch.empty((B, M), dtype=torch.float32, device="cuda")
+    keep = torch.empty((B, 1), dtype=torch.int32, device="cuda")
+    fv.fvar_score_select(ctx, to_dev(x, dtype), B, M, 1, keep, None, scores_out=s)
+    torch.cuda.synchronize()
+    sg = to_np(s)
+    return all(np.array_equal(sg[b], oracle.scores(x[b])) for b in range(B))
+
+
+def first_clean_seed(draw_x, dtype: str, seed: int, tries: int = 4) -> int:
+    """First seed of seed, seed+7919, ... whose activations draw_x(seed) give bit-identical scores
+    on both sides (see gpu_scores_identical)."""
+    for t in range(tries):
+        if gpu_scores_identical(draw_x(seed + 7919 * t), dtype):
+            return seed + 7919 * t
+    raise AssertionError(f"{tries} consecutive seeds gave a score that differs from the oracle")
+
+
 def check_scores_and_indices(s_gpu, keep_gpu, drop_gpu, x, k):
     """Scores and index sets of one sample against the oracle.
 

@@ -130,6 +130,29 @@ def test_entry_points_reject_bad_arguments_without_launching():
     assert lib.fvar_cache_factors(h, None, fake, fake, 0, 2, 64, 16, 0.0, fake, fake, fake, need - 1) == fv.FVAR_ERR_WORKSPACE
 
 
+def test_block_calls_reject_operands_beyond_32bit_tile_offsets():
+    """The linear-layer kernels address an operand matrix with 32-bit byte offsets: a call whose
+    widest operand (B*rows x max(hidden, ffn_hidden) elements) reaches 4 GiB must be refused
+    before anything is launched, not wrap silently."""
+    lib = fv.load_library()
+    c = fv.Context(hidden=2048, heads=16, head_dim=128, ffn_hidden=8192, dtype="bf16")
+    h, fake = c.handle, 0x1000
+    w = fv._Weights()
+    for n, _ in fv._Weights._fields_:
+        setattr(w, n, None)
+    for n in ("w_qkv", "w_o", "w_fc1", "w_fc2"):
+        setattr(w, n, fake)
+    kv = fv._KV(fake, fake, 1 << 20, 0)
+    # 64 x 4096 rows x 8192 columns x 2 bytes = 4 GiB exactly: refused
+    assert lib.fvar_block_forward_dense(h, None, C.byref(w), fake, 64, 4096, C.byref(kv), fake, fake, 1 << 60) == fv.FVAR_ERR_UNSUPPORTED
+    assert b"4 GiB" in lib.fvar_last_error(h)
+    # one row less per sample is inside the limit: the call gets as far as the workspace check
+    assert lib.fvar_block_forward_dense(h, None, C.byref(w), fake, 64, 4095, C.byref(kv), fake, fake, 16) == fv.FVAR_ERR_WORKSPACE
+    # batch beyond the launch grid's third dimension (8 key ranges per sample)
+    assert lib.fvar_block_forward_dense(h, None, C.byref(w), fake, 8192, 8, C.byref(kv), fake, fake, 1 << 60) == fv.FVAR_ERR_UNSUPPORTED
+    assert lib.fvar_debug_checks(h, 1) == fv.FVAR_OK and lib.fvar_debug_checks(h, 0) == fv.FVAR_OK
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(fv, "_lib", None)
     monkeypatch.setattr(fv, "LIB_PATH", "/nonexistent/libfvar.so")
