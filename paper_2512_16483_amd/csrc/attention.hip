@@ -8,11 +8,17 @@
 //     per tile), the rescale of the output accumulator is a per-lane multiply, and the
 //     probabilities are already laid out as the B operand of the second product
 //     O^T = V^T P^T -- no trip through LDS for P.
-//   * K tiles go to LDS row-major (swizzled 16 B chunks).  V tiles are transposed on their way
-//     into LDS with a register 4x8 transpose (v_perm_b32), stored [Dh][t'] where t' orders the
-//     keys the way the accumulator layout hands out P, so the V^T operand is one ds_read_b128.
-//   * global -> register prefetch of the next K/V tile overlaps the MFMAs of the current one;
-//     LDS is double buffered, one barrier per tile.
+//   * K and V tiles travel global -> LDS directly (global_load_lds_dwordx4, no staging registers,
+//     no LDS store instructions), both row-major with XOR-swizzled 16-byte chunks; the swizzle is
+//     applied on the global side (which chunk a lane fetches), since the DMA writes LDS in lane
+//     order.  K rows feed the A operand of S^T with one ds_read_b128.  The A operand of the second
+//     product needs V transposed (8 consecutive keys of one head-dim column per lane): it is read
+//     with the transposing LDS load (ds_read_b64_tr_b16), which hands a lane 4 elements of one
+//     column out of the 16 row chunks its 16-lane group points at -- V is never transposed in
+//     memory.  The rows each lane points at follow the order in which the accumulator layout
+//     hands out the keys of P.
+//   * LDS is double buffered: the DMA of the next tile runs under the MFMAs of the current one,
+//     one barrier per tile.
 //
 // fp32 kernel: plain tiled FMA version for the fp32 parity configuration.
 #include <type_traits>
@@ -23,26 +29,32 @@ namespace fvar {
 
 constexpr int BT = 64;                       // keys per tile
 
-typedef int intx4_t __attribute__((ext_vector_type(4)));
+typedef short shortx4_t __attribute__((ext_vector_type(4)));
+typedef short shortx8_t __attribute__((ext_vector_type(8)));
 
-// 16-byte global load whose position in the instruction stream is fixed.  The compiler does not
-// count this load: the destination must be kept alive and unread until an explicit
-// s_waitcnt vmcnt that the later uses are tied to (see wait_tile below).
-__device__ __forceinline__ intx4_t global_load_b128(const void *base, uint32_t byte_off)
+// 16 bytes per lane global -> LDS; the wavefront fills 1 KiB starting at `lds_addr` in lane order.
+// M0 carries the LDS base and is rewritten before every use; no other instruction of these
+// kernels reads it.  The loads are counted by hand (s_waitcnt vmcnt) because the compiler does
+// not see them.
+__device__ __forceinline__ void attn_dma_b128(const void *base, uint32_t byte_off, uint32_t lds_addr)
 {
-    intx4_t v;
-    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(v) : "v"(byte_off), "s"(base) : "memory");
-    return v;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory", "m0");
 }
 
-// Chunk swizzle of the V^T tile (rows = head-dim index, 8 chunks of 8 keys).  Readers fetch 16
-// consecutive rows at one logical chunk: (row/2)%8 makes those 16 accesses cover all 64 banks
-// once, and the extra term is constant inside an aligned group of 16 rows, so it keeps that.
-// Writers store 8-byte halves to rows 8 apart (one per 8-column block of the transposed 4x8
-// blocks): the extra term, a function of row/16, spreads those rows over different chunks.
-__device__ __forceinline__ int vt_swz(int row)
+// Chunk swizzles (XOR on the 16-byte chunk index of a row).
+//   K rows are read 16 rows at a time at one logical chunk (ds_read_b128): with 256-byte rows
+//   (head_dim 128) all rows start at the same bank, so the 16 rows must land in 16 different
+//   chunks; with 128-byte rows two neighbouring rows already differ by half the banks.
+//   V rows are read by the transposing load 4 consecutive rows x 64 contiguous bytes at a time
+//   (per 32 lanes): the 4 rows must land in different 64-byte quarters of the 256-byte bank span.
+template <int DH> __device__ __forceinline__ int k_swz(int row)
 {
-    return ((row >> 1) & 7) ^ (((row >> 4) & 1) << 2) ^ ((row >> 5) & 3);
+    return DH == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+template <int DH> __device__ __forceinline__ int v_swz(int row)
+{
+    return DH == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
 
 template <int DH, int NQ>
@@ -57,16 +69,17 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
 {
     constexpr int KS = DH / 16;              // k16 steps of the QK product
     constexpr int DB = DH / 32;              // 32-row blocks of O^T
-    constexpr int KCH = DH / 8;              // 16 B chunks per K row
-    constexpr int LK = BT * KCH / 256;       // K chunks per thread per tile
-    constexpr int VBLK = (BT / 4) * (DH / 8);        // 4x8 transpose blocks per V tile
-    constexpr int LV = (VBLK + 255) / 256;       // V blocks per thread
+    constexpr int KCH = DH / 8;              // 16 B chunks per K / V row
+    constexpr int RPD = 64 / KCH;            // tile rows filled by one DMA instruction (1 KiB)
+    constexpr int NDMA = BT / RPD / 4;       // DMA instructions per wavefront per tile and tensor
     constexpr int KTILE = BT * DH, STAGE = 2 * KTILE;
 
     extern __shared__ uint4 lds_raw[];
-    uint16_t *lds = reinterpret_cast<uint16_t *>(lds_raw);   // [stage][K tile | V^T tile]
+    uint16_t *lds = reinterpret_cast<uint16_t *>(lds_raw);   // [stage][K tile | V tile]
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds_raw;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rl = lane & 31, g = lane >> 5;
     // blockIdx.z = sample * nsplit + split: with nsplit > 1 this workgroup sees only the key tiles
     // [tile0, tile1) and leaves an unnormalised partial result for the merge kernel
@@ -88,116 +101,51 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
             qf[j][s] = *reinterpret_cast<const bf16x8_t *>(src + 16 * s);
     }
 
-    // ---- staging assignment
-    int k_row[LK], k_chk[LK];
+    // ---- DMA assignment: wavefront w owns the 1 KiB row groups w, w+4, ... of each tile; lane l
+    // fills physical chunk l % KCH of tile row RPD*group + l / KCH, i.e. it fetches the logical
+    // chunk that the swizzle maps there.  Byte offsets from the tile's first row; a tile that
+    // reaches past row L-1 recomputes them with the row clamped.
+    int d_row[NDMA];
+    uint32_t k_off[NDMA], v_off[NDMA];
 #pragma unroll
-    for (int i = 0; i < LK; ++i) {
-        const int id = tid + 256 * i;
-        k_row[i] = id / KCH;
-        k_chk[i] = id % KCH;
+    for (int i = 0; i < NDMA; ++i) {
+        d_row[i] = (wave + 4 * i) * RPD + lane / KCH;
+        const int pc = lane % KCH;
+        k_off[i] = (uint32_t)(((size_t)d_row[i] * rowpitch + ((pc ^ k_swz<DH>(d_row[i])) << 3)) * 2);
+        v_off[i] = (uint32_t)(((size_t)d_row[i] * rowpitch + ((pc ^ v_swz<DH>(d_row[i])) << 3)) * 2);
     }
-    // V block: 4 key rows x 8 head-dim columns.  tb4 = 2*chunk + half; chunk = 2*w + gg covers
-    // keys 16w + 8a + 4gg + jj (a = half, jj = 0..3): the order in which a lane's accumulator
-    // entries enumerate the keys of a 16-key MFMA step.
-    // When the tile has fewer blocks than threads (head_dim 64) the upper threads repeat the
-    // lower ones' blocks: same loads, same LDS stores, no divergence.
-    int v_t0[LV], v_col[LV], v_dst[LV];
-#pragma unroll
-    for (int i = 0; i < LV; ++i) {
-        const int blk = (tid + 256 * i) % VBLK;
-        const int cb = blk % (DH / 8), tb4 = blk / (DH / 8);
-        const int chunk = tb4 >> 1, a = tb4 & 1, w = chunk >> 1, gg = chunk & 1;
-        v_t0[i] = 16 * w + 8 * a + 4 * gg;
-        v_col[i] = cb * 8;
-        v_dst[i] = chunk * 8 + a * 4;        // element offset inside an unswizzled V^T row
-    }
-
-    // The tile loads are issued through asm so that they stay where they are written (the
-    // compiler would sink them next to the LDS stores); their registers are read only after the
-    // explicit vmcnt wait further down the same straight-line block.
-    intx4_t kreg[LK];
-    intx4_t vreg[LV][4];
-    // byte offsets of this thread's chunks inside a tile that lies wholly inside the cache: such a
-    // tile is fetched as (uniform tile base) + (these constants); only a tile that reaches past
-    // row L-1 pays for the per-row clamp
-    uint32_t k_off[LK], v_off[LV][4];
-#pragma unroll
-    for (int i = 0; i < LK; ++i) k_off[i] = (uint32_t)(((size_t)k_row[i] * rowpitch + k_chk[i] * 8) * 2);
-#pragma unroll
-    for (int i = 0; i < LV; ++i)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
-            v_off[i][jj] = (uint32_t)(((size_t)(v_t0[i] + jj) * rowpitch + v_col[i]) * 2);
-    auto load_tile = [&](int t0) {
+    auto issue_tile = [&](int t0, int stage) {
+        const uint32_t sk = lds_base + stage * (STAGE * 2) + wave * 1024, sv = sk + KTILE * 2;
         if (t0 + BT <= L) {                                  // uniform
             const uint16_t *kt = Kb + (size_t)t0 * rowpitch, *vtile = Vb + (size_t)t0 * rowpitch;
 #pragma unroll
-            for (int i = 0; i < LK; ++i) kreg[i] = global_load_b128(kt, k_off[i]);
+            for (int i = 0; i < NDMA; ++i) attn_dma_b128(kt, k_off[i], sk + i * 4096);
 #pragma unroll
-            for (int i = 0; i < LV; ++i)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) vreg[i][jj] = global_load_b128(vtile, v_off[i][jj]);
+            for (int i = 0; i < NDMA; ++i) attn_dma_b128(vtile, v_off[i], sv + i * 4096);
             return;
         }
 #pragma unroll
-        for (int i = 0; i < LK; ++i) {
-            const int t = min(t0 + k_row[i], L - 1);
-            kreg[i] = global_load_b128(Kb, (uint32_t)(((size_t)t * rowpitch + k_chk[i] * 8) * 2));
+        for (int i = 0; i < NDMA; ++i) {
+            const int t = min(t0 + d_row[i], L - 1), pc = lane % KCH;
+            attn_dma_b128(Kb, (uint32_t)(((size_t)t * rowpitch + ((pc ^ k_swz<DH>(d_row[i])) << 3)) * 2),
+                          sk + i * 4096);
         }
 #pragma unroll
-        for (int i = 0; i < LV; ++i) {
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const int t = min(t0 + v_t0[i] + jj, L - 1);
-                vreg[i][jj] = global_load_b128(Vb, (uint32_t)(((size_t)t * rowpitch + v_col[i]) * 2));
-            }
+        for (int i = 0; i < NDMA; ++i) {
+            const int t = min(t0 + d_row[i], L - 1), pc = lane % KCH;
+            attn_dma_b128(Vb, (uint32_t)(((size_t)t * rowpitch + ((pc ^ v_swz<DH>(d_row[i])) << 3)) * 2),
+                          sv + i * 4096);
         }
     };
-    // Wait for the asm loads and make every later use of the staging registers depend on that
-    // wait: the empty asm statements "redefine" the registers, so neither the ALU work of the
-    // transpose nor a reuse of the registers can be scheduled while the loads are in flight.
-    auto wait_tile = [&]() {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int i = 0; i < LK; ++i) asm volatile("" : "+v"(kreg[i]));
-#pragma unroll
-        for (int i = 0; i < LV; ++i)
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) asm volatile("" : "+v"(vreg[i][jj]));
-    };
-    // Lanes of odd column blocks store the odd row of each row pair first, so that one store
-    // instruction touches rows of both parities (both halves of the 64 banks); which half of the
-    // byte permute goes first is folded into per-thread selector constants.
-    uint32_t v_sel[LV][2];
-#pragma unroll
-    for (int i = 0; i < LV; ++i) {
-        const bool flip = (v_col[i] >> 3) & 1;
-        v_sel[i][0] = flip ? 0x07060302u : 0x05040100u;
-        v_sel[i][1] = flip ? 0x05040100u : 0x07060302u;
-    }
-    auto store_tile = [&](uint16_t *st) {
-#pragma unroll
-        for (int i = 0; i < LK; ++i)
-            *reinterpret_cast<intx4_t *>(st + k_row[i] * DH + ((k_chk[i] ^ ((k_row[i] >> 1) & 7)) << 3)) =
-                kreg[i];
-        uint16_t *vt = st + KTILE;
-#pragma unroll
-        for (int i = 0; i < LV; ++i) {
-            const int chunk = v_dst[i] >> 3, sub = v_dst[i] & 7;
-            const int par = (v_col[i] >> 3) & 1;
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                uint2 first, second;
-                first.x = __builtin_amdgcn_perm(vreg[i][1][m], vreg[i][0][m], v_sel[i][0]);
-                first.y = __builtin_amdgcn_perm(vreg[i][3][m], vreg[i][2][m], v_sel[i][0]);
-                second.x = __builtin_amdgcn_perm(vreg[i][1][m], vreg[i][0][m], v_sel[i][1]);
-                second.y = __builtin_amdgcn_perm(vreg[i][3][m], vreg[i][2][m], v_sel[i][1]);
-                const int ra = v_col[i] + 2 * m + par, rb = v_col[i] + 2 * m + (par ^ 1);
-                *reinterpret_cast<uint2 *>(vt + ra * BT + ((chunk ^ vt_swz(ra)) << 3) + sub) = first;
-                *reinterpret_cast<uint2 *>(vt + rb * BT + ((chunk ^ vt_swz(rb)) << 3) + sub) = second;
-            }
-        }
-    };
+
+    // ---- transposing V read: lane l = 16*G + 4*j + a points at key row 4*(G/2) + j (+ 16u + 8h) and
+    // the 4 head-dim values 16*(G%2) + 4*a (+ 32*db); it receives, for the output row
+    // 16*(G%2) + (l%16) of block db, the keys 4*(G/2) + 0..3 (+ 16u + 8h): the k-slots 4h..4h+3 of
+    // half G/2, in the order the P fragments hold them
+    const int tG = lane >> 4, tj = (lane >> 2) & 3, ta = lane & 3;
+    const int v_row = 4 * (tG >> 1) + tj;                    // key row inside a 16-key step (h = 0)
+    const int v_swq = v_swz<DH>(v_row) >> 2;                 // depends on the lane only (rows +8, +16 keep it)
+    const int v_lane = v_row * DH + ((2 * (tG & 1) + (ta >> 1)) << 3) + (ta & 1) * 4;   // elements
 
     floatx16_t oacc[DB][NQ];
 #pragma unroll
@@ -210,9 +158,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
 
     const int tile0 = split * tiles_per_split;
     const int tile1 = min((L + BT - 1) / BT, tile0 + tiles_per_split);
-    load_tile(tile0 * BT);
-    wait_tile();
-    store_tile(lds);
+    const int nloc = tile1 - tile0;
+    issue_tile(tile0 * BT, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     // the Q fragments are consumed here once so that the compiler's own wait for their loads
     // sits in front of the loop instead of inside it (where it would also wait for the prefetch)
 #pragma unroll
@@ -228,8 +176,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
         const int it = tile0 + lt;
         const uint16_t *ks = lds + (lt & 1) * STAGE;
         const uint16_t *vt = ks + KTILE;
-        // next tile (row indices are clamped, so the request past the end is harmless)
-        load_tile((it + 1) * BT);
+        // next tile into the other stage: every wavefront finished reading it before the barrier
+        // that ended the previous iteration
+        if (lt + 1 < nloc) issue_tile((it + 1) * BT, (lt + 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
 
         // a wavefront whose queries all lie past the end only helps with the staging
@@ -246,7 +195,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
             for (int tb = 0; tb < 2; ++tb) {
                 const int r = tb * 32 + rl;
                 const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(
-                    ks + r * DH + (((2 * s + g) ^ ((r >> 1) & 7)) << 3));
+                    ks + r * DH + (((2 * s + g) ^ k_swz<DH>(r)) << 3));
 #pragma unroll
                 for (int j = 0; j < NQ; ++j)
                     sacc[tb][j] =
@@ -313,9 +262,12 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
         for (int u = 0; u < 4; ++u) {
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                const int dr = db * 32 + rl;
-                const bf16x8_t vf = *reinterpret_cast<const bf16x8_t *>(
-                    vt + dr * BT + (((2 * u + g) ^ vt_swz(dr)) << 3));
+                typedef __attribute__((address_space(3))) shortx4_t lds_shortx4_t;
+                const uint16_t *vsrc = vt + v_lane + 16 * u * DH + ((db ^ v_swq) << 5);
+                const shortx4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_t *)vsrc);
+                const shortx4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_t *)(vsrc + 8 * DH));
+                const shortx8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);
 #pragma unroll
                 for (int j = 0; j < NQ; ++j)
                     oacc[db][j] =
@@ -323,11 +275,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
             }
         }
         }
-        wait_tile();
-        store_tile(lds + ((lt + 1) & 1) * STAGE);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     };
-    const int nloc = tile1 - tile0;
     for (int lt = 0; lt + 1 < nloc; ++lt) tile(lt, std::false_type{});
     tile(nloc - 1, std::true_type{});
 

@@ -205,7 +205,7 @@ __device__ __forceinline__ void store_tile_epilogue(const floatx16_t (*acc)[FN],
 __device__ __forceinline__ void dma_b128(const void *base, uint32_t byte_off, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
+                 :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory", "m0");
 }
 
 // LDS needed after the main loop: k-split reduction buffer + one staging tile per wavefront.
