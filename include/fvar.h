@@ -39,7 +39,9 @@
  *    are then undefined.  fvar_last_error() returns a text for the last failing
  *    call on that context.
  *  - A context may be used from one thread at a time.  State outside a context:
- *    a thread-local pointer that exists only while a call with per-kernel
+ *    a per-device table of the address of the built-in scratch array used by
+ *    fvar_score_select_static (filled under a mutex on a device's first call),
+ *    and a thread-local pointer that exists only while a call with per-kernel
  *    timing switched on is enqueueing its kernels.
  *  - Index arrays are int32, strictly ascending per sample and in range; this is
  *    the caller's contract for fvar_block_forward_pruned / fvar_lowrank_fill /
@@ -144,6 +146,18 @@ size_t fvar_block_workspace_bytes(const fvar_ctx *ctx, int32_t B, int32_t rows);
 fvar_status fvar_score_select(fvar_ctx *ctx, fvar_stream stream, const void *x, int32_t B,
                               int32_t M, int32_t k, const float *scores_in, float *scores_out,
                               int32_t *idx_keep, int32_t *idx_drop, void *ws, size_t ws_bytes);
+
+/* The same selection for callers that cannot allocate device memory or carry a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * scores live in a fixed device array built into the library (4 MiB per GPU, held until the
+ * process ends) instead of caller workspace.  No hipMalloc / hipFree, no workspace argument.
+ * Requires B*M <= 1048576 (FVAR_ERR_UNSUPPORTED beyond that; use fvar_score_select).  x is
+ * required; results are bit-identical to fvar_score_select.  Every call on one GPU uses the
+ * same array: calls that overlap in time on one GPU (different streams or threads) race and
+ * must be serialised by the caller.  The array keeps the previous call's scores; a call
+ * rewrites every entry it reads, so nothing is cleared. */
+fvar_status fvar_score_select_static(fvar_ctx *ctx, fvar_stream stream, const void *x, int32_t B,
+                                     int32_t M, int32_t k, int32_t *idx_keep, int32_t *idx_drop);
 
 /* Vanilla block on every token of the scale (paper, Alg. "FasterVAR", establishment stages:
  * F_k^o = phi(F~_{k-1})).  x:[B,M,d] -> y:[B,M,d]; writes M new K/V rows per sample at

@@ -22,7 +22,7 @@ EXPORTS = (
     "fvar_block_forward_pruned", "fvar_lowrank_fill", "fvar_rp_project", "fvar_cache_fill",
     "fvar_factors_workspace_bytes", "fvar_cache_factors", "fvar_upsample_tokens",
     "fvar_profile_enable",
-    "fvar_profile_read", "fvar_debug_checks",
+    "fvar_profile_read", "fvar_debug_checks", "fvar_score_select_static",
 )
 
 
@@ -104,6 +104,8 @@ def load_library() -> C.CDLL:
     lib.fvar_cache_factors.restype = C.c_int
     lib.fvar_upsample_tokens.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
     lib.fvar_upsample_tokens.restype = C.c_int
+    lib.fvar_score_select_static.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.fvar_score_select_static.restype = C.c_int
     lib.fvar_debug_checks.argtypes = [vp, i32]
     lib.fvar_debug_checks.restype = C.c_int
     lib.fvar_profile_enable.argtypes = [vp, i32]
@@ -204,6 +206,12 @@ def fvar_score_select(ctx: Context, x, B: int, M: int, k: int, idx_keep, idx_dro
     ctx.check(ctx.lib.fvar_score_select(ctx.handle, _stream(stream), _ptr(x), B, M, k,
                                         _ptr(scores_in), _ptr(scores_out), _ptr(idx_keep),
                                         _ptr(idx_drop), _ptr(ws), _nbytes(ws)))
+
+
+def fvar_score_select_static(ctx: Context, x, B: int, M: int, k: int, idx_keep, idx_drop=None,
+                             stream=None) -> None:
+    ctx.check(ctx.lib.fvar_score_select_static(ctx.handle, _stream(stream), _ptr(x), B, M, k,
+                                               _ptr(idx_keep), _ptr(idx_drop)))
 
 
 def fvar_debug_checks(ctx: Context, on: bool) -> None:

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -14,6 +15,15 @@
 using fvar::DType;
 
 thread_local fvar::LaunchProbe *fvar::g_probe = nullptr;
+
+// Scratch of fvar_score_select_static (the fp32 scores of one call): a fixed device array instead
+// of caller workspace, so that the call needs no allocation anywhere.  Every GPU the library runs
+// on holds its own copy; host code reaches it only through the per-device address below.
+constexpr int kStaticScoreCap = 1 << 20;                       // floats: 4 MiB per device
+static __device__ __align__(256) float scratch[kStaticScoreCap];
+constexpr int kMaxDevices = 64;
+static float *g_scratch_ptr[kMaxDevices];                      // resolved on a device's first call
+static std::mutex g_scratch_mutex;
 
 struct fvar_ctx {
     fvar_config cfg;
@@ -409,6 +419,41 @@ fvar_status fvar_score_select(fvar_ctx *c, fvar_stream stream, const void *x, in
         if (e != hipSuccess) return fail(c, FVAR_ERR_HIP, "%s: %s", who, hipGetErrorString(e));
     }
     timed(c, st, "select", [&] { fvar::launch_select(scores, B, M, k, idx_keep, idx_drop, st); });
+    return launch_status(c, who);
+}
+
+fvar_status fvar_score_select_static(fvar_ctx *c, fvar_stream stream, const void *x, int32_t B,
+                                     int32_t M, int32_t k, int32_t *idx_keep, int32_t *idx_drop)
+{
+    if (!c) return FVAR_ERR_INVALID_ARG;
+    const char *who = "fvar_score_select_static";
+    if (B < 1 || M < 1 || k < 1 || k > M)
+        return fail(c, FVAR_ERR_INVALID_ARG, "%s: need B>=1 and 1<=k<=M (B=%d M=%d k=%d)", who, B, M, k);
+    if ((int64_t)B * M > kStaticScoreCap)
+        return fail(c, FVAR_ERR_UNSUPPORTED, "%s: B*M = %lld exceeds the built-in scratch of %d scores; use "
+                    "fvar_score_select with a workspace", who, (long long)B * M, kStaticScoreCap);
+    if (!x || !idx_keep) return fail(c, FVAR_ERR_INVALID_ARG, "%s: x or idx_keep is NULL", who);
+    if (!aligned16(x)) return fail(c, FVAR_ERR_INVALID_ARG, "%s: pointer not 16-byte aligned", who);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return fail(c, FVAR_ERR_HIP, "%s: no usable current device", who);
+    float *buf;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            // the array's name is only a host-side handle; this is its address on the current device
+            float *p = nullptr;
+            const hipError_t e = hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p)
+                return fail(c, FVAR_ERR_HIP, "%s: hipGetSymbolAddress: %s", who, hipGetErrorString(e));
+            g_scratch_ptr[dev] = p;
+        }
+        buf = g_scratch_ptr[dev];
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // every score of [0, B*M) is rewritten before the selection reads it: nothing to clear
+    timed(c, st, "score", [&] { fvar::launch_scores(dtype(c), x, B * M, c->cfg.hidden, buf, st); });
+    timed(c, st, "select", [&] { fvar::launch_select(buf, B, M, k, idx_keep, idx_drop, st); });
     return launch_status(c, who);
 }
 

@@ -150,6 +150,9 @@ def test_block_calls_reject_operands_beyond_32bit_tile_offsets():
     assert lib.fvar_block_forward_dense(h, None, C.byref(w), fake, 64, 4095, C.byref(kv), fake, fake, 16) == fv.FVAR_ERR_WORKSPACE
     # batch beyond the launch grid's third dimension (8 key ranges per sample)
     assert lib.fvar_block_forward_dense(h, None, C.byref(w), fake, 8192, 8, C.byref(kv), fake, fake, 1 << 60) == fv.FVAR_ERR_UNSUPPORTED
+    # the selection without workspace: size limit and argument checks need no GPU either
+    assert lib.fvar_score_select_static(h, None, fake, 1025, 1024, 4, fake, None) == fv.FVAR_ERR_UNSUPPORTED
+    assert lib.fvar_score_select_static(h, None, fake, 1, 8, 9, fake, None) == fv.FVAR_ERR_INVALID_ARG
     assert lib.fvar_debug_checks(h, 1) == fv.FVAR_OK and lib.fvar_debug_checks(h, 0) == fv.FVAR_OK
 
 
