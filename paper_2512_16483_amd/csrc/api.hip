@@ -164,8 +164,8 @@ BlockWs carve(const fvar_ctx *c, void *ws, int B, int rows)
     w.h1 = take(R * d * sizeof(float));       // intermediate residual stream, always fp32
     w.hid = take(R * F * es);
     // partial attention results when the key axis is split between workgroups (small batches)
-    const int splits = fvar::attention_max_splits(dtype(c), B, rows, c->cfg.heads, c->cfg.head_dim);
-    w.att_part = splits > 1 ? take((size_t)splits * R * (d + 2 * c->cfg.heads) * sizeof(float)) : nullptr;
+    const size_t part = fvar::attention_scratch_floats(dtype(c), B, rows, c->cfg.heads, c->cfg.head_dim);
+    w.att_part = part ? take(part * sizeof(float)) : nullptr;
     // partial tiles of the linear layers whose contraction axis is divided between workgroups
     const DType dt = dtype(c);
     size_t gp = 0;

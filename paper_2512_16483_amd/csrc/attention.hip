@@ -65,7 +65,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
                                                         uint16_t *__restrict__ o, int nsplit,
                                                         int tiles_per_split,
                                                         float *__restrict__ part_o,
-                                                        float *__restrict__ part_ml)
+                                                        float *__restrict__ part_ml, int nqb,
+                                                        int full_units, int tail_split)
 {
     constexpr int KS = DH / 16;              // k16 steps of the QK product
     constexpr int DB = DH / 32;              // 32-row blocks of O^T
@@ -81,10 +82,39 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rl = lane & 31, g = lane >> 5;
-    // blockIdx.z = sample * nsplit + split: with nsplit > 1 this workgroup sees only the key tiles
-    // [tile0, tile1) and leaves an unnormalised partial result for the merge kernel
-    const int h = blockIdx.y, b = blockIdx.z / nsplit, split = blockIdx.z % nsplit;
-    const int q0 = blockIdx.x * (128 * NQ) + wave * (32 * NQ);
+    // Work decomposition.  A unit is one (query block, head, sample) triple, numbered with the
+    // query block fastest.  Two ways of dividing the key axis between workgroups exist:
+    //  * nsplit > 1 (problems with too few units to fill the chip): every unit is divided into
+    //    nsplit key ranges, workgroup id = (sample * nsplit + range) * H * nqb + head * nqb + block;
+    //  * tail_split > 1 (many units, but the last round of workgroups would leave most of the chip
+    //    idle): the first full_units units run whole, each later unit is divided into tail_split
+    //    ranges.
+    // A workgroup with a partial key range [tile0, tile1) leaves an unnormalised partial result
+    // (O, running max, running sum) for a merge kernel.
+    int unit = blockIdx.x, split = 0, ranges = 1;
+    size_t prow_base = 0;                                    // partial row of query 0 of this unit
+    int prow_stride = 0;
+    if (nsplit > 1) {
+        const int per = H * nqb, zz = unit / per;
+        split = zz % nsplit;
+        ranges = nsplit;
+        unit = (zz / nsplit) * per + unit % per;
+    } else if (unit >= full_units) {
+        const int t = unit - full_units;
+        unit = full_units + t / tail_split;
+        split = t % tail_split;
+        ranges = tail_split;
+    }
+    const int qb = unit % nqb, h = (unit / nqb) % H, b = unit / (nqb * H);
+    if (nsplit > 1) {
+        prow_base = (size_t)(b * nsplit + split) * n * H + h;
+        prow_stride = H;
+    } else if (ranges > 1) {
+        prow_base = (size_t)((unit - full_units) * tail_split + split) * (128 * NQ) -
+                    (size_t)qb * (128 * NQ);
+        prow_stride = 1;
+    }
+    const int q0 = qb * (128 * NQ) + wave * (32 * NQ);
     const bool wave_active = __builtin_amdgcn_readfirstlane(q0 < n ? 1 : 0) != 0;
     const size_t rowpitch = (size_t)H * DH;
     const uint16_t *Kb = Kc + ((size_t)b * cap * H + h) * DH;
@@ -156,8 +186,9 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
 #pragma unroll
     for (int j = 0; j < NQ; ++j) { m_run[j] = -INFINITY; l_run[j] = 0.f; }
 
-    const int tile0 = split * tiles_per_split;
-    const int tile1 = min((L + BT - 1) / BT, tile0 + tiles_per_split);
+    const int ntiles_all = (L + BT - 1) / BT;
+    const int tile0 = ranges > 1 ? split * tiles_per_split : 0;
+    const int tile1 = ranges > 1 ? min(ntiles_all, tile0 + tiles_per_split) : ntiles_all;
     const int nloc = tile1 - tile0;
     issue_tile(tile0 * BT, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -189,19 +220,43 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int j = 0; j < NQ; ++j) sacc[tb][j] = floatx16_t{0};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
+        // operand fragments are fetched one step ahead of the MFMAs that use them
+        auto load_k = [&](int s, bf16x8_t *dst) {
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb) {
                 const int r = tb * 32 + rl;
-                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(
+                dst[tb] = *reinterpret_cast<const bf16x8_t *>(
                     ks + r * DH + (((2 * s + g) ^ k_swz<DH>(r)) << 3));
+            }
+        };
+        auto load_v = [&](int u, bf16x8_t *dst) {
+            typedef __attribute__((address_space(3))) shortx4_t lds_shortx4_t;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const uint16_t *vsrc = vt + v_lane + 16 * u * DH + ((db ^ v_swq) << 5);
+                const shortx4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_t *)vsrc);
+                const shortx4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_t *)(vsrc + 8 * DH));
+                dst[db] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+        };
+        bf16x8_t kf[2][2];
+        load_k(0, kf[0]);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            if (s + 1 < KS) load_k(s + 1, kf[(s + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
                 for (int j = 0; j < NQ; ++j)
-                    sacc[tb][j] =
-                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[j][s], sacc[tb][j], 0, 0, 0);
-            }
+                    sacc[tb][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s & 1][tb], qf[j][s],
+                                                                          sacc[tb][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // the first V fragments travel under the softmax
+        bf16x8_t vf[2][DB];
+        load_v(0, vf[0]);
+        __builtin_amdgcn_sched_barrier(0);
         // ---- mask the ragged tail of the cache
         if (MASKED) {
             const int t0 = it * BT;
@@ -260,19 +315,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
         // ---- O^T += V^T P^T
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
+            if (u + 1 < 4) load_v(u + 1, vf[(u + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                typedef __attribute__((address_space(3))) shortx4_t lds_shortx4_t;
-                const uint16_t *vsrc = vt + v_lane + 16 * u * DH + ((db ^ v_swq) << 5);
-                const shortx4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_t *)vsrc);
-                const shortx4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_t *)(vsrc + 8 * DH));
-                const shortx8_t v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int j = 0; j < NQ; ++j)
-                    oacc[db][j] =
-                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u][j], oacc[db][j], 0, 0, 0);
-            }
+                    oacc[db][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u & 1][db], pf[u][j],
+                                                                          oacc[db][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -281,14 +332,14 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
     for (int lt = 0; lt + 1 < nloc; ++lt) tile(lt, std::false_type{});
     tile(nloc - 1, std::true_type{});
 
-    if (nsplit > 1) {
+    if (ranges > 1) {
         // partial result of this key range: unnormalised O (fp32), running max and sum
 #pragma unroll
         for (int j = 0; j < NQ; ++j) {
             const int row = q0 + j * 32 + rl;
             const float l = l_run[j] + __shfl_xor(l_run[j], 32);
             if (row >= n) continue;
-            const size_t prow = ((size_t)(b * nsplit + split) * n + row) * H + h;
+            const size_t prow = prow_base + (size_t)row * prow_stride;
             float *dst = part_o + prow * DH;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -358,6 +409,67 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
     *reinterpret_cast<uint2 *>(o + ((size_t)brow * H + h) * DH + c4 * 4) = pk;
 }
 
+// Merge for the units whose key axis was divided only in the last round of workgroups: partials
+// are stored per (tail unit, range) as [BQ queries][DH] (+ [BQ][2] running max / sum).
+// One thread per 4 consecutive head-dim values of one (tail unit, query).
+__global__ __launch_bounds__(256) void attn_tail_merge_kernel(const float *__restrict__ part_o,
+                                                              const float *__restrict__ part_ml, int n,
+                                                              int H, int DH, int BQ, int nqb,
+                                                              int full_units, int ranges, float c_log2,
+                                                              long total, uint16_t *__restrict__ o)
+{
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;       // over tail units * BQ * DH/4
+    if (idx >= total) return;
+    const int c4 = (int)(idx % (DH / 4));
+    const long uq = idx / (DH / 4);
+    const int ql = (int)(uq % BQ), tu = (int)(uq / BQ), unit = full_units + tu;
+    const int qb = unit % nqb, h = (unit / nqb) % H, b = unit / (nqb * H);
+    const int row = qb * BQ + ql;
+    if (row >= n) return;
+    float m = -INFINITY;
+    for (int s = 0; s < ranges; ++s) m = fmaxf(m, part_ml[((size_t)(tu * ranges + s) * BQ + ql) * 2]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float den = 0.f;
+    for (int s = 0; s < ranges; ++s) {
+        const size_t prow = (size_t)(tu * ranges + s) * BQ + ql;
+        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + prow * 2);
+        const float w = __builtin_amdgcn_exp2f((ml.x - m) * c_log2);
+        const float4 v = *reinterpret_cast<const float4 *>(part_o + prow * DH + c4 * 4);
+        acc.x = fmaf(v.x, w, acc.x); acc.y = fmaf(v.y, w, acc.y);
+        acc.z = fmaf(v.z, w, acc.z); acc.w = fmaf(v.w, w, acc.w);
+        den = fmaf(ml.y, w, den);
+    }
+    const float inv = 1.0f / den;
+    uint2 pk;
+    pk.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+    pk.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+    *reinterpret_cast<uint2 *>(o + (((size_t)b * n + row) * H + h) * DH + c4 * 4) = pk;
+}
+
+// Query rows per workgroup and workgroups that a CU holds at once for a problem (the variant the
+// launcher picks), and the plan for the last round of workgroups: with `units` workgroups on
+// `slots` places, the units beyond the last full round are divided into `ranges` key ranges each
+// when that round would leave more than a quarter of the places empty.
+struct AttnPlan { int bq, slots, nqb, units, full_units, tail_ranges; };
+static AttnPlan attention_plan(int B, int n, int H, int Dh)
+{
+    AttnPlan p;
+    const bool wide = Dh == 64 && ((n % 256 == 0) || (n % 256 > 128));
+    p.bq = wide ? 256 : 128;
+    p.slots = 256 * ((Dh == 64 && !wide) ? 4 : 2);
+    p.nqb = (n + p.bq - 1) / p.bq;
+    p.units = p.nqb * H * B;
+    p.full_units = p.units / p.slots * p.slots;
+    const int rem = p.units - p.full_units;
+    p.tail_ranges = 1;
+    if (p.full_units > 0 && rem > 0 && rem * 4 <= p.slots * 3) {
+        int r = p.slots / rem;
+        p.tail_ranges = r > 8 ? 8 : r;
+    }
+    if (p.tail_ranges < 2) { p.tail_ranges = 1; p.full_units = p.units; }
+    return p;
+}
+
 // Number of key ranges for a problem, from the launch geometry alone (not the cache length, so
 // that the workspace can be sized from it; the launcher lowers it when the cache is short).
 // The kernel is throughput-bound per CU, so what counts is rounds of workgroups over the 256 CUs:
@@ -380,6 +492,18 @@ int attention_max_splits(DType dt, int B, int n, int H, int Dh)
     return best;
 }
 
+// Floats of scratch the bf16 attention of a problem may need for partial results (either way of
+// dividing the key axis); 0 when every workgroup sees the whole cache.
+size_t attention_scratch_floats(DType dt, int B, int n, int H, int Dh)
+{
+    if (dt != DType::BF16) return 0;
+    const int ns = attention_max_splits(dt, B, n, H, Dh);
+    if (ns > 1) return (size_t)ns * B * n * H * (Dh + 2);
+    const AttnPlan p = attention_plan(B, n, H, Dh);
+    if (p.tail_ranges > 1) return (size_t)(p.units - p.full_units) * p.tail_ranges * p.bq * (Dh + 2);
+    return 0;
+}
+
 template <int DH, int NQ>
 static void launch_attn_bf16(const void *q, const void *K, const void *V, int B, int n, int L,
                              int cap, int H, float scale, void *o, float *part, hipStream_t st)
@@ -397,17 +521,33 @@ static void launch_attn_bf16(const void *q, const void *K, const void *V, int B,
     int tps = (ntiles + nsplit - 1) / nsplit;
     nsplit = (ntiles + tps - 1) / tps;
     const float c_log2 = scale * 1.4426950408889634f;
-    float *part_o = part;
-    float *part_ml = part ? part + (size_t)nsplit * B * n * H * DH : nullptr;
-    dim3 grid((n + BQ - 1) / BQ, H, B * nsplit), block(256);
-    launch(kern, grid, block, lds, st, (const uint16_t *)q, (const uint16_t *)K,
-                       (const uint16_t *)V, n, L, cap, H, c_log2, (uint16_t *)o, nsplit, tps, part_o,
-                       part_ml);
+    AttnPlan plan = attention_plan(B, n, H, DH);
+    int tail = (part && nsplit == 1) ? plan.tail_ranges : 1;
+    if (tail > ntiles / 4) tail = ntiles / 4 > 0 ? ntiles / 4 : 1;
+    if (tail > 1) {
+        tps = (ntiles + tail - 1) / tail;
+        tail = (ntiles + tps - 1) / tps;
+    }
+    if (tail < 2) { tail = 1; plan.full_units = plan.units; }
+    const int tail_units = plan.units - plan.full_units;
+    float *part_o = part, *part_ml = nullptr;
+    if (nsplit > 1) part_ml = part + (size_t)nsplit * B * n * H * DH;
+    else if (tail > 1) part_ml = part + (size_t)tail_units * tail * BQ * DH;
+    const unsigned nwg = nsplit > 1 ? (unsigned)plan.units * nsplit
+                                    : (unsigned)(plan.full_units + tail_units * tail);
+    launch(kern, dim3(nwg), dim3(256), lds, st, (const uint16_t *)q, (const uint16_t *)K,
+           (const uint16_t *)V, n, L, cap, H, c_log2, (uint16_t *)o, nsplit, tps, part_o, part_ml,
+           plan.nqb, plan.full_units, tail);
     if (nsplit > 1) {
         const long total = (long)B * n * H * (DH / 4);
         launch(attn_merge_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                (const float *)part_o, (const float *)part_ml, n, H, DH, nsplit, c_log2, total,
                (uint16_t *)o);
+    } else if (tail > 1) {
+        const long total = (long)tail_units * BQ * (DH / 4);
+        launch(attn_tail_merge_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+               (const float *)part_o, (const float *)part_ml, n, H, DH, BQ, plan.nqb, plan.full_units,
+               tail, c_log2, total, (uint16_t *)o);
     }
 }
 

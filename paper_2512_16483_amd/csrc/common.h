@@ -143,11 +143,11 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
 
 // o[b,i,h,:] = softmax_t(scale * q[b,i,h,:] . K[b,t,h,:]) V[b,t,h,:], t in [0,L)
 //   q,o:[B,n,H,Dh]; K,V:[B,cap,H,Dh]
-// `part`: scratch for splitting the key axis between workgroups when the problem has too few
-// (query block, head, sample) triples to fill the chip, or null (never split):
-// attention_max_splits() * B*n*H*(Dh + 2) floats.  With more than one key range a second kernel
-// merges the partial results.
-int attention_max_splits(DType dt, int B, int n, int H, int Dh);
+// `part`: scratch of attention_scratch_floats() floats for dividing the key axis between workgroups
+// (every unit of a problem with too few (query block, head, sample) triples to fill the chip, or
+// only the units of the last, mostly empty round of workgroups of a large problem), or null
+// (never divide).  With more than one key range a second kernel merges the partial results.
+size_t attention_scratch_floats(DType dt, int B, int n, int H, int Dh);
 void launch_attention(DType dt, const void *q, const void *K, const void *V, int B, int n, int L,
                       int cap, int H, int Dh, float scale, void *o, float *part, hipStream_t st);
 

@@ -197,6 +197,29 @@ def test_runs_are_deterministic(case):
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
 
 
+@pytest.mark.parametrize("H,k", [(4, 4200), (4, 4300), (2, 4200)])
+def test_attention_last_round_divided_between_workgroups(H, k):
+    """Many (query block, head, sample) triples whose count is just above a multiple of what the
+    chip holds at once: the triples of the last round of workgroups are divided along the key
+    axis and merged.  Three kernel variants (head_dim 64 with one and two query blocks per
+    wavefront, head_dim 128); every sample is compared with the oracle, the divided triples are
+    those of the last sample."""
+    dtype, B, d, F, Lp, r = "bf16", 8, 256, 256, 2100, 8
+    M = k + 50
+    x, w, Kp, Vp, Wc, Gc = make_case(dtype, B, M, d, H, F, Lp, r, seed=900 + k + H)
+    ref = oracle_pruned(x, k, w, H, Kp, Vp, Wc, Gc)
+    blk = GpuBlock(d, H, F, dtype, w, Kp, Vp, Lp + M)
+    xd = to_dev(x, dtype)
+    s, keep, drop = blk.score_select(xd, k)
+    y_keep = blk.pruned(xd, keep, k)
+    torch.cuda.synchronize()
+    same_scores(s, keep, drop, x, k, ref)
+    for b in range(B):
+        e = rel_err(to_np(y_keep[b]), ref["y_keep"][b])
+        assert e <= TOL[dtype], (b, e)
+    assert rel_err(to_np(blk.K[:, Lp:Lp + k]), ref["K_new"]) <= TOL[dtype]
+
+
 # ----------------------------------------------------------------------------- real shapes
 def test_var_d16_last_scale_fp32_full():
     """The fp32 configuration at its full size: 256 tokens, 424 cached rows, keep 0.5, r = 32."""
