@@ -192,6 +192,21 @@ fvar_status fvar_lowrank_fill(fvar_ctx *ctx, fvar_stream stream, const void *y_k
                               int32_t M, int32_t k, int32_t r, const void *w_c, const void *g_c,
                               void *y);
 
+/* The same restoration that also returns the row energies of the map it writes,
+ *   scores_out[b,i] = fl32(sum_j y[b,i,j]^2)   (exact products of the stored elements, fp64 sum),
+ * i.e. the selection scores of the NEXT block (paper, Sec. "Representative Token Restoration":
+ * rows are ranked by the energy of the block input, and this map is the next block's input):
+ * fvar_score_select can then run with scores_in = scores_out and never reads the map.  The
+ * kernels that write y accumulate the energy of what they store per 128-column slab; a second
+ * small kernel adds the slabs in a fixed order, so the result is deterministic and, like
+ * fvar_score_select's own scores, equal to the exactly rounded sum except in double-rounding
+ * corner cases.  scores_out:[B,M] fp32.  ws: at least fvar_fill_scored_workspace_bytes(ctx,B,M). */
+size_t fvar_fill_scored_workspace_bytes(const fvar_ctx *ctx, int32_t B, int32_t M);
+fvar_status fvar_lowrank_fill_scored(fvar_ctx *ctx, fvar_stream stream, const void *y_keep,
+                                     const int32_t *idx_keep, const int32_t *idx_drop, int32_t B,
+                                     int32_t M, int32_t k, int32_t r, const void *w_c, const void *g_c,
+                                     void *y, float *scores_out, void *ws, size_t ws_bytes);
+
 /* Random projection to r rows (paper, Sec. "Random Projection (RP) for Low-Rank Feature":
  * F^_r = Q^T F~ with Q in R^{M x r}, Q_ij ~ N(0, 1/r); Alg. "FasterVAR", fidelity stage).
  *   out[b,t,:] = sum_i qt[t,i] * x[b,i,:]

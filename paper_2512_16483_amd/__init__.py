@@ -23,6 +23,7 @@ EXPORTS = (
     "fvar_factors_workspace_bytes", "fvar_cache_factors", "fvar_upsample_tokens",
     "fvar_profile_enable",
     "fvar_profile_read", "fvar_debug_checks", "fvar_score_select_static",
+    "fvar_fill_scored_workspace_bytes", "fvar_lowrank_fill_scored",
 )
 
 
@@ -94,6 +95,10 @@ def load_library() -> C.CDLL:
     lib.fvar_block_forward_pruned.restype = C.c_int
     lib.fvar_lowrank_fill.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.fvar_lowrank_fill.restype = C.c_int
+    lib.fvar_fill_scored_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.fvar_fill_scored_workspace_bytes.restype = sz
+    lib.fvar_lowrank_fill_scored.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz]
+    lib.fvar_lowrank_fill_scored.restype = C.c_int
     lib.fvar_rp_project.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, vp]
     lib.fvar_rp_project.restype = C.c_int
     lib.fvar_cache_fill.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, vp, vp]
@@ -246,6 +251,18 @@ def fvar_lowrank_fill(ctx: Context, y_keep, idx_keep, idx_drop, B: int, M: int, 
                       w_c, g_c, y, stream=None) -> None:
     ctx.check(ctx.lib.fvar_lowrank_fill(ctx.handle, _stream(stream), _ptr(y_keep), _ptr(idx_keep),
                                         _ptr(idx_drop), B, M, k, r, _ptr(w_c), _ptr(g_c), _ptr(y)))
+
+
+def fvar_fill_scored_workspace_bytes(ctx: Context, B: int, M: int) -> int:
+    return ctx.lib.fvar_fill_scored_workspace_bytes(ctx.handle, B, M)
+
+
+def fvar_lowrank_fill_scored(ctx: Context, y_keep, idx_keep, idx_drop, B: int, M: int, k: int, r: int,
+                             w_c, g_c, y, scores_out, ws, stream=None) -> None:
+    ctx.check(ctx.lib.fvar_lowrank_fill_scored(ctx.handle, _stream(stream), _ptr(y_keep),
+                                               _ptr(idx_keep), _ptr(idx_drop), B, M, k, r, _ptr(w_c),
+                                               _ptr(g_c), _ptr(y), _ptr(scores_out), _ptr(ws),
+                                               _nbytes(ws)))
 
 
 def fvar_rp_project(ctx: Context, qt, q_per_sample: bool, x, B: int, M: int, rows: int, out,

@@ -476,12 +476,11 @@ fvar_status fvar_block_forward_pruned(fvar_ctx *c, fvar_stream stream, const fva
                          ws_bytes, "fvar_block_forward_pruned");
 }
 
-fvar_status fvar_lowrank_fill(fvar_ctx *c, fvar_stream stream, const void *y_keep,
-                              const int32_t *idx_keep, const int32_t *idx_drop, int32_t B, int32_t M,
-                              int32_t k, int32_t r, const void *w_c, const void *g_c, void *y)
+static fvar_status lowrank_fill(fvar_ctx *c, fvar_stream stream, const void *y_keep,
+                                const int32_t *idx_keep, const int32_t *idx_drop, int32_t B, int32_t M,
+                                int32_t k, int32_t r, const void *w_c, const void *g_c, void *y,
+                                float *scores_out, void *ws, size_t ws_bytes, const char *who)
 {
-    if (!c) return FVAR_ERR_INVALID_ARG;
-    const char *who = "fvar_lowrank_fill";
     if (B < 1 || M < 1 || k < 0 || k > M)
         return fail(c, FVAR_ERR_INVALID_ARG, "%s: need B>=1 and 0<=k<=M (B=%d M=%d k=%d)", who, B, M, k);
     if (!y || (k > 0 && !y_keep)) return fail(c, FVAR_ERR_INVALID_ARG, "%s: null output or y_keep", who);
@@ -494,8 +493,18 @@ fvar_status fvar_lowrank_fill(fvar_ctx *c, fvar_stream stream, const void *y_kee
             return fail(c, FVAR_ERR_INVALID_ARG, "%s: rank %d must be in [1,256] and a multiple of %d",
                         who, r, mult);
     }
-    if (!aligned16(y) || !aligned16(y_keep) || !aligned16(w_c) || !aligned16(g_c))
+    if (!aligned16(y) || !aligned16(y_keep) || !aligned16(w_c) || !aligned16(g_c) || !aligned16(ws))
         return fail(c, FVAR_ERR_INVALID_ARG, "%s: pointer not 16-byte aligned", who);
+    if ((int64_t)B * M > (int64_t)INT32_MAX / 2)
+        return fail(c, FVAR_ERR_UNSUPPORTED, "%s: B*M too large", who);
+    double *parts = nullptr;
+    if (scores_out) {
+        const size_t need = fvar_fill_scored_workspace_bytes(c, B, M);
+        if (!ws || ws_bytes < need)
+            return fail(c, FVAR_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given", who, need,
+                        ws_bytes);
+        parts = static_cast<double *>(ws);
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (c->debug_checks && k < M) {
         const fvar_status vs = validate_indices(c, st, idx_keep, idx_drop, B, M, k, who);
@@ -503,9 +512,36 @@ fvar_status fvar_lowrank_fill(fvar_ctx *c, fvar_stream stream, const void *y_kee
     }
     timed(c, st, "fill", [&] {
         fvar::launch_fill(dtype(c), y_keep, idx_keep, idx_drop, B, M, k, r, c->cfg.hidden, w_c, g_c, y,
-                          st);
+                          parts, scores_out, st);
     });
     return launch_status(c, who);
+}
+
+size_t fvar_fill_scored_workspace_bytes(const fvar_ctx *c, int32_t B, int32_t M)
+{
+    if (!c || B < 1 || M < 1) return 0;
+    return align256((size_t)B * M * fvar::fill_score_parts(dtype(c), c->cfg.hidden) * sizeof(double));
+}
+
+fvar_status fvar_lowrank_fill(fvar_ctx *c, fvar_stream stream, const void *y_keep,
+                              const int32_t *idx_keep, const int32_t *idx_drop, int32_t B, int32_t M,
+                              int32_t k, int32_t r, const void *w_c, const void *g_c, void *y)
+{
+    if (!c) return FVAR_ERR_INVALID_ARG;
+    return lowrank_fill(c, stream, y_keep, idx_keep, idx_drop, B, M, k, r, w_c, g_c, y, nullptr, nullptr,
+                        0, "fvar_lowrank_fill");
+}
+
+fvar_status fvar_lowrank_fill_scored(fvar_ctx *c, fvar_stream stream, const void *y_keep,
+                                     const int32_t *idx_keep, const int32_t *idx_drop, int32_t B,
+                                     int32_t M, int32_t k, int32_t r, const void *w_c, const void *g_c,
+                                     void *y, float *scores_out, void *ws, size_t ws_bytes)
+{
+    if (!c) return FVAR_ERR_INVALID_ARG;
+    if (!scores_out)
+        return fail(c, FVAR_ERR_INVALID_ARG, "fvar_lowrank_fill_scored: scores_out is NULL");
+    return lowrank_fill(c, stream, y_keep, idx_keep, idx_drop, B, M, k, r, w_c, g_c, y, scores_out, ws,
+                        ws_bytes, "fvar_lowrank_fill_scored");
 }
 
 fvar_status fvar_rp_project(fvar_ctx *c, fvar_stream stream, const void *qt, int32_t q_per_sample,

@@ -152,9 +152,12 @@ void launch_attention(DType dt, const void *q, const void *K, const void *V, int
                       int cap, int H, int Dh, float scale, void *o, float *part, hipStream_t st);
 
 // y[b,idx_keep[b,j],:] = y_keep[b,j,:];  y[b,i,:] = w_c[b,i,:] g_c[b] for i in idx_drop[b,:]
+// parts / scores_out: null, or scratch of B*M*fill_score_parts() doubles and a [B*M] fp32 array that
+// receives the energy (sum of squares of the stored elements) of every row of y
+int fill_score_parts(DType dt, int d);
 void launch_fill(DType dt, const void *y_keep, const int32_t *idx_keep, const int32_t *idx_drop,
                  int B, int M, int k, int r, int d, const void *w_c, const void *g_c, void *y,
-                 hipStream_t st);
+                 double *parts, float *scores_out, hipStream_t st);
 
 // raw-cache variant of the fill: pruned rows are copied from cache:[B,M,d]
 void launch_cache_fill(DType dt, const void *y_keep, const int32_t *idx_keep, const int32_t *idx_drop,

@@ -87,6 +87,30 @@ class GpuBlock:
         return y
 
 
+def fill_scored(blk, y_keep, idx_keep, idx_drop, M, Wc, Gc):
+    """fvar_lowrank_fill_scored: the map and the row energies of the map (the next block's scores)."""
+    B, k, d = y_keep.shape
+    y = torch.full((B, M, d), float("nan"), dtype=y_keep.dtype, device="cuda")
+    scores = torch.full((B, M), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(fv.fvar_fill_scored_workspace_bytes(blk.ctx, B, M), dtype=torch.uint8, device="cuda")
+    r = Gc.shape[1] if Gc is not None else 0
+    fv.fvar_lowrank_fill_scored(blk.ctx, y_keep, idx_keep, idx_drop, B, M, k, r, Wc, Gc, y, scores, ws)
+    return y, scores
+
+
+def check_scores_of_map(scores_gpu: np.ndarray, y_gpu: np.ndarray) -> None:
+    """Scores that a kernel reports for a map it wrote, against the oracle's scores of exactly that
+    map (the stored values): bit-identical up to the double-rounding allowance (a few rows one ulp
+    apart, see check_scores_and_indices)."""
+    so = oracle.scores(np.ascontiguousarray(y_gpu, np.float32))
+    sg = np.asarray(scores_gpu, np.float32)
+    diff = np.flatnonzero(sg != so)
+    assert diff.size <= max(1, so.size // 100000 + 1), f"{diff.size} of {so.size} scores differ"
+    if diff.size:
+        ulp = np.abs(sg[diff].view(np.int32).astype(np.int64) - so[diff].view(np.int32).astype(np.int64))
+        assert ulp.max() <= 1
+
+
 def oracle_pruned(x, k, weights, H, Kp, Vp, Wc, Gc):
     """Oracle over the batch; returns dict of stacked outputs and the appended K/V rows."""
     B, M, d = x.shape

@@ -12,7 +12,8 @@ import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-from gpu_util import (TOL, GpuBlock, check_scores_and_indices, check_map, first_clean_seed,  # noqa: E402
+from gpu_util import (TOL, GpuBlock, check_scores_and_indices, check_map, check_scores_of_map,  # noqa: E402
+                      fill_scored, first_clean_seed,
                       oracle_dense, oracle_pruned, rel_err, report, tdtype, to_dev, to_np)
 
 
@@ -116,6 +117,46 @@ def test_lowrank_fill(dtype, r, M, d, k):
         ref = oracle.lowrank_fill(yk[b], keep[b], drop[b], M, Wc[b], Gc[b])
         assert np.array_equal(y[b][keep[b]], yk[b])                       # kept rows are copies
         assert rel_err(y[b], ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,r,M,d,k", [("bf16", 64, 300, 1920, 120), ("bf16", 128, 700, 4096, 200),
+                                           ("bf16", 8, 129, 256, 129), ("bf16", 24, 130, 192, 0),
+                                           ("bf16", 200, 97, 320, 5), ("f32", 32, 200, 1024, 77),
+                                           ("f32", 4, 64, 128, 64)])
+def test_lowrank_fill_scored(dtype, r, M, d, k):
+    """The restoration that also reports the row energies of the map it writes: same map as the
+    plain call bit for bit, and scores equal to the oracle's scores of that stored map."""
+    bf = dtype == "bf16"
+    B = 3
+    rng = np.random.default_rng(7 * r + M)
+    Wc = rng.standard_normal((B, M, r)).astype(np.float32)
+    Gc = (rng.standard_normal((B, r, d)) / np.sqrt(r)).astype(np.float32)
+    yk = (rng.standard_normal((B, k, d)) * np.exp(rng.standard_normal((B, k, 1)))).astype(np.float32)
+    if bf:
+        Wc, Gc, yk = wl.round_to_bf16(Wc), wl.round_to_bf16(Gc), wl.round_to_bf16(yk)
+    keep = np.stack([np.sort(rng.permutation(M)[:k]) for _ in range(B)]).astype(np.int32).reshape(B, k)
+    drop = np.stack([np.setdiff1d(np.arange(M), keep[b]) for b in range(B)]).astype(np.int32)
+    blk = GpuBlock(d, d // 64, 256, dtype, {}, np.zeros((B, 0, d // 64, 64), np.float32),
+                   np.zeros((B, 0, d // 64, 64), np.float32), 1)
+    args = (to_dev(yk, dtype), torch.from_numpy(keep).cuda(), torch.from_numpy(drop).cuda(), M,
+            to_dev(Wc, dtype), to_dev(Gc, dtype))
+    y_plain = blk.fill(*args)
+    y, scores = fill_scored(blk, *args)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_plain)
+    yh, sh = to_np(y), to_np(scores)
+    assert np.isfinite(sh).all()
+    for b in range(B):
+        check_scores_of_map(sh[b], yh[b])
+        ref = oracle.lowrank_fill(yk[b], keep[b], drop[b], M, Wc[b], Gc[b])
+        assert rel_err(yh[b], ref) <= TOL[dtype]
+    # the next block's selection from these scores is the selection from the map itself
+    kk = max(1, M // 3)
+    s2, keep2, drop2 = blk.score_select(y, kk)
+    _, keep3, drop3 = blk.score_select(y, kk, scores_in=scores)
+    torch.cuda.synchronize()
+    if np.array_equal(to_np(s2), sh):
+        assert torch.equal(keep2, keep3) and torch.equal(drop2, drop3)
 
 
 # ----------------------------------------------------------------------------- block, small shapes
