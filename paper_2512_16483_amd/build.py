@@ -12,7 +12,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfvar.so")
 SOURCES = ["api.hip", "score_select.hip", "rows.hip", "gemm.hip", "attention.hip", "fill.hip",
            "rp.hip", "factors.hip", "upsample.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          # packed-fp32 VALU forms are kept off for every device pass
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

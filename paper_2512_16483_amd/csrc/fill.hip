@@ -192,8 +192,11 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(const uint16_t *__restri
                     pk.y = pack_bf16x2(acc[c2][4 * q + 2], acc[c2][4 * q + 3]);
                     *reinterpret_cast<uint2 *>(wl + rl * kFillStage + c2 * 32 + 8 * q + 4 * g) = pk;
                 }
-            // same wavefront wrote and reads the region: LDS operations of a wavefront stay in order.
+            // same wavefront wrote and reads the region: LDS operations of a wavefront stay in order
+            // in hardware; the compiler is told not to move them across these points (the stores
+            // and loads use different vector types).
             // 8 lanes cover the 128 bytes of one row half: 8 rows per store instruction.
+            asm volatile("" ::: "memory");
             const int c = (lane & 7) * 8;
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
@@ -202,15 +205,22 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(const uint16_t *__restri
                 const int col = col0 + half * 64 + c;
                 const bool ok = rr < nd && col < d;
                 if (ok) *reinterpret_cast<uint4 *>(Y + (size_t)drop[rr] * d + col) = v;
-                if (parts) erow[it] += group_sum(ok ? chunk_energy<uint16_t>(v) : 0.0, 8);
+                if (parts && ok) erow[it] += chunk_energy<uint16_t>(v);
             }
+            asm volatile("" ::: "memory");
         }
-        // the lane at the head of each 8-lane group owns rows it*8 + lane/8 of the group
+        // the 8 lanes of a group hold the pieces of one row; the lane at their head owns rows
+        // it*8 + lane/8 of the group
+        double e8[4];
+        if (parts) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) e8[it] = group_sum(erow[it], 8);
+        }
         if (parts && (lane & 7) == 0) {
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 const int rr = j0 + it * 8 + (lane >> 3);
-                if (rr < nd) parts[((size_t)b * M + drop[rr]) * slabs + slab] = erow[it];
+                if (rr < nd) parts[((size_t)b * M + drop[rr]) * slabs + slab] = e8[it];
             }
         }
     };
