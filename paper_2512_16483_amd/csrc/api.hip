@@ -171,8 +171,8 @@ BlockWs carve(const fvar_ctx *c, void *ws, int B, int rows)
     size_t gp = 0;
     const size_t shapes[3][2] = {{d, d}, {F, d}, {d, F}};            // (N, K) of O, FC1, FC2
     for (auto &sh : shapes) {
-        const int ns = fvar::gemm_splits(dt, (int)R, (int)sh[0], (int)sh[1]);
-        if (ns > 1 && ns * R * sh[0] * sizeof(float) > gp) gp = ns * R * sh[0] * sizeof(float);
+        const size_t need = fvar::gemm_scratch_floats(dt, (int)R, (int)sh[0], (int)sh[1]) * sizeof(float);
+        if (need > gp) gp = need;
     }
     w.gemm_part = gp ? take(gp) : nullptr;
     w.total = off;

@@ -133,11 +133,12 @@ struct GemmEpilogue {
     // Used for the intermediate residual stream h = x + attention projection, which stays in
     // fp32 between the two halves of the block so that it is not rounded twice.
     int out_f32 = 0, res_f32 = 0;
-    // bf16 path: scratch for dividing the contraction axis between workgroups when the problem
-    // has too few tiles to fill the chip, gemm_splits() * rows * N floats, or null (never divide).
+    // bf16 path: scratch of gemm_scratch_floats() floats for dividing the contraction axis between
+    // workgroups (every tile of a problem with too few tiles to fill the chip, or only the tiles
+    // beyond the last full round of workgroups), or null (never divide).
     float *splitk_scratch = nullptr;
 };
-int gemm_splits(DType dt, int rows, int N, int K);
+size_t gemm_scratch_floats(DType dt, int rows, int N, int K);
 void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
                  const GemmEpilogue &ep, hipStream_t st);
 

@@ -78,58 +78,38 @@ __device__ __forceinline__ void store_tile_epilogue(const floatx16_t (*acc)[FN],
     constexpr int TM = FM * 32, TN = FN * 32, PITCH = TN + 8;
     const int rl = lane & 31, g = lane >> 5;
     const uint16_t *bias = reinterpret_cast<const uint16_t *>(ep.bias);
-    if (ep.out_f32) {
-        // fp32 output (never routed, never GELU-ed; the residual operand is bf16)
+    if constexpr (F32_STAGED) {
+        // fp32 output (never routed, never GELU-ed; the residual operand is bf16): same two-phase
+        // scheme with an fp32 staging tile, 16-byte (4 float) row chunks out
         const uint16_t *res = reinterpret_cast<const uint16_t *>(ep.residual);
         float *out = reinterpret_cast<float *>(ep.out0);
-        if constexpr (F32_STAGED) {
-            // same two-phase scheme with an fp32 staging tile: 16-byte (4 float) row chunks out
-            constexpr int P32 = TN + 4;
-            float *w32 = reinterpret_cast<float *>(wlds);
+        constexpr int P32 = TN + 4;
+        float *w32 = reinterpret_cast<float *>(wlds);
 #pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int col = wcol0 + j * 32 + rl;
-                const float bv = (bias && col < N) ? bf16_to_f32(bias[col]) : 0.f;
+        for (int j = 0; j < FN; ++j) {
+            const int col = wcol0 + j * 32 + rl;
+            const float bv = (bias && col < N) ? bf16_to_f32(bias[col]) : 0.f;
 #pragma unroll
-                for (int i = 0; i < FM; ++i)
+            for (int i = 0; i < FM; ++i)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        w32[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * P32 + j * 32 + rl] =
-                            acc[i][j][e] + bv;
-            }
-            constexpr int CPR = TN / 4, RPI = 64 / CPR;
-            const int lc = (lane % CPR) * 4, col = wcol0 + lc;
-#pragma unroll
-            for (int it = 0; it < TM / RPI; ++it) {
-                const int lrow = it * RPI + lane / CPR, row = wrow0 + lrow;
-                float4 v = *reinterpret_cast<const float4 *>(w32 + lrow * P32 + lc);
-                if (row >= rows || col >= N) continue;
-                if (res) {
-                    const uint2 rv = *reinterpret_cast<const uint2 *>(res + (size_t)row * N + col);
-                    v.x += bf16_lo(rv.x); v.y += bf16_hi(rv.x); v.z += bf16_lo(rv.y); v.w += bf16_hi(rv.y);
-                }
-                *reinterpret_cast<float4 *>(out + (size_t)row * ep.ld0 + col) = v;
-            }
-        } else {
-            // staging tile too large for LDS: the 32 lanes of a half-wavefront still cover 128
-            // contiguous bytes of one row, so store the accumulators directly
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int col = wcol0 + j * 32 + rl;
-                if (col >= N) continue;
-                const float bv = bias ? bf16_to_f32(bias[col]) : 0.f;
-#pragma unroll
-                for (int i = 0; i < FM; ++i)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int row = wrow0 + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                        if (row >= rows) continue;
-                        float v = acc[i][j][e] + bv;
-                        if (res) v += bf16_to_f32(res[(size_t)row * N + col]);
-                        out[(size_t)row * ep.ld0 + col] = v;
-                    }
-            }
+                for (int e = 0; e < 16; ++e)
+                    w32[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * P32 + j * 32 + rl] = acc[i][j][e] + bv;
         }
+        asm volatile("" ::: "memory");       // staging stores and loads use different vector types
+        constexpr int CPR = TN / 4, RPI = 64 / CPR;
+        const int lc = (lane % CPR) * 4, col = wcol0 + lc;
+#pragma unroll
+        for (int it = 0; it < TM / RPI; ++it) {
+            const int lrow = it * RPI + lane / CPR, row = wrow0 + lrow;
+            float4 v = *reinterpret_cast<const float4 *>(w32 + lrow * P32 + lc);
+            if (row >= rows || col >= N) continue;
+            if (res) {
+                const uint2 rv = *reinterpret_cast<const uint2 *>(res + (size_t)row * N + col);
+                v.x += bf16_lo(rv.x); v.y += bf16_hi(rv.x); v.z += bf16_lo(rv.y); v.w += bf16_hi(rv.y);
+            }
+            *reinterpret_cast<float4 *>(out + (size_t)row * ep.ld0 + col) = v;
+        }
+        asm volatile("" ::: "memory");
         return;
     }
     const int odd = lane & 1;
@@ -153,7 +133,9 @@ __device__ __forceinline__ void store_tile_epilogue(const floatx16_t (*acc)[FN],
         }
     }
     // the region is private to this wavefront and LDS operations of one wavefront complete in
-    // order, so no barrier is needed between the two phases
+    // order, so no barrier is needed between the two phases (the compiler is kept from moving the
+    // accesses across this point: the stores and loads use different vector types)
+    asm volatile("" ::: "memory");
     constexpr int CPR = TN / 8, RPI = 64 / CPR;             // chunks per row, rows per instruction
     const uint16_t *res = reinterpret_cast<const uint16_t *>(ep.residual);
     const bool routed = ep.split < N;                       // K/V columns go to the cache
@@ -194,6 +176,7 @@ __device__ __forceinline__ void store_tile_epilogue(const floatx16_t (*acc)[FN],
         }
         *reinterpret_cast<uint4 *>(dst) = v;
     }
+    asm volatile("" ::: "memory");
 }
 
 // The operand tiles travel global -> LDS directly (global_load_lds_dwordx4: 16 bytes per lane, a
@@ -209,22 +192,31 @@ __device__ __forceinline__ void dma_b128(const void *base, uint32_t byte_off, ui
 }
 
 // LDS needed after the main loop: k-split reduction buffer + one staging tile per wavefront.
-// A wavefront whose sub-tile is taller than 128 rows sends it through the epilogue in two parts
-// (epi_frags() 32-row fragments at a time), so its staging tile never exceeds 128 rows.
+// A wavefront sends its sub-tile through the epilogue in passes of a few 32-row fragments:
+// epi_frags() for bf16 output (a staging tile of at most 128 rows), epi_frags_f32() for fp32
+// output (as many fragments as fit the LDS with 4-byte elements, at least one).
 constexpr size_t kLdsLimit = 160 * 1024;
 constexpr size_t gemm_red_bytes(int BM, int BN, int KS) { return KS > 1 ? (size_t)BM * BN * 4 : 0; }
 constexpr int epi_frags(int FM) { return FM > 4 ? (FM + 1) / 2 : FM; }
-constexpr int epi_rows(int BM, int WM) { return 32 * epi_frags(BM / WM / 32) * WM; }   // all wavefronts
-constexpr bool gemm_f32_staging_fits(int BM, int BN, int WM, int WN, int KS)
+constexpr size_t epi_bytes_bf16(int BM, int BN, int WM, int WN)
 {
-    return gemm_red_bytes(BM, BN, KS) + (size_t)epi_rows(BM, WM) * (BN / WN + 4) * WN * 4 <= kLdsLimit;
+    return (size_t)32 * epi_frags(BM / WM / 32) * (BN / WN + 8) * 2 * WM * WN;
+}
+constexpr size_t epi_bytes_f32(int BN, int WM, int WN, int fe)
+{
+    return (size_t)32 * fe * (BN / WN + 4) * 4 * WM * WN;
+}
+constexpr int epi_frags_f32(int BM, int BN, int WM, int WN, int KS)
+{
+    int fe = epi_frags(BM / WM / 32);
+    while (fe > 1 && gemm_red_bytes(BM, BN, KS) + epi_bytes_f32(BN, WM, WN, fe) > kLdsLimit) --fe;
+    return fe;
 }
 constexpr size_t gemm_epi_lds_bytes(int BM, int BN, int WM, int WN, int KS)
 {
-    return gemm_red_bytes(BM, BN, KS) +
-           (gemm_f32_staging_fits(BM, BN, WM, WN, KS)
-                ? (size_t)epi_rows(BM, WM) * (BN / WN + 4) * WN * 4
-                : (size_t)epi_rows(BM, WM) * (BN / WN + 8) * WN * 2);
+    const size_t a = epi_bytes_bf16(BM, BN, WM, WN);
+    const size_t b = epi_bytes_f32(BN, WM, WN, epi_frags_f32(BM, BN, WM, WN, KS));
+    return gemm_red_bytes(BM, BN, KS) + (a > b ? a : b);
 }
 
 // KS > 1 splits every k-tile between KS groups of WM x WN wavefronts (group ks takes the 16-wide
@@ -233,7 +225,8 @@ constexpr size_t gemm_epi_lds_bytes(int BM, int BN, int WM, int WN, int KS)
 template <int BM, int BN, int WM, int WN, int STAGES, int KS>
 __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, int rows, int N, int K,
-    int tiles_m, int tiles_n, int group_m, EpiParams ep, int nsplit, float *__restrict__ part)
+    int tiles_m, int tiles_n, int group_m, EpiParams ep, int nsplit, float *__restrict__ part,
+    int full_tiles, int tail_split)
 {
     constexpr int NW = WM * WN * KS;                   // wavefronts per workgroup
     constexpr int TM = BM / WM, TN = BN / WN;
@@ -244,15 +237,40 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     extern __shared__ uint4 lds_raw[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds_raw;
 
-    // nsplit > 1: the contraction axis is divided between nsplit workgroups per tile (for problems
-    // with too few tiles to fill the chip); each leaves an fp32 partial tile in `part` and a
-    // second kernel adds them up and applies the epilogue
+    // Work decomposition.  Workgroups are dealt to the 8 XCDs round-robin; XCD x takes the x-th
+    // eighth of the work in ascending order.  Three modes:
+    //  * plain: one workgroup per tile;
+    //  * nsplit > 1 (too few tiles to fill the chip): the contraction axis of every tile is divided
+    //    between nsplit workgroups, partial tiles go to `part` in the output's [rows][N] layout;
+    //  * tail_split > 1 (the tiles beyond the last full round of 256 would leave most CUs idle):
+    //    the first full_tiles tiles run whole, each later tile is divided between tail_split
+    //    workgroups whose partial tiles go to `part` tile by tile; every XCD gets an eighth of
+    //    the whole tiles first and an eighth of the divided ones after them.
+    // Partial tiles are summed and finished by a second kernel.
     const int ntiles = tiles_m * tiles_n;
-    const int per_xcd = (gridDim.x + 7) / 8;
-    int pid = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (pid >= ntiles * nsplit) return;
-    const int split = pid % nsplit;
-    pid /= nsplit;
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    int pid, split = 0, ranges = 1;
+    if (tail_split > 1) {
+        const int nf = full_tiles / 8, tail_units = (ntiles - full_tiles) * tail_split;
+        const int nt = (tail_units + 7) / 8;
+        if (slot < nf) {
+            pid = xcd * nf + slot;
+        } else {
+            const int t = xcd * nt + (slot - nf);
+            if (slot - nf >= nt || t >= tail_units) return;
+            pid = full_tiles + t / tail_split;
+            split = t % tail_split;
+            ranges = tail_split;
+        }
+    } else {
+        const int per_xcd = (gridDim.x + 7) / 8;
+        pid = xcd * per_xcd + slot;
+        if (pid >= ntiles * nsplit) return;
+        split = pid % nsplit;
+        pid /= nsplit;
+        ranges = nsplit;
+    }
+    const int tile_id = pid;
     // consecutive tile ids run down group_m row tiles, then across the columns: the contiguous
     // id range of one XCD is a patch of about group_m x (tiles/8/group_m) tiles
     const int group = pid / (group_m * tiles_n);
@@ -284,7 +302,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
         const int c = (lane & 7) ^ ((r >> 1) & 7);
         b_off[i] = (uint32_t)(((size_t)min(col0 + r, N - 1) * K + c * 8) * sizeof(uint16_t));
     }
-    const int ktiles_all = K / BK, kper = (ktiles_all + nsplit - 1) / nsplit;
+    const int ktiles_all = K / BK, kper = (ktiles_all + ranges - 1) / ranges;
     const int kt0 = split * kper;
     const int ktiles = min(ktiles_all, kt0 + kper) - kt0;   // k-tiles of this workgroup (>= 1)
     auto issue = [&](int kt, int stage) {               // DMA of this workgroup's k-tile kt into `stage`
@@ -380,46 +398,116 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] += red[((i * FN + j) * 16 + e) * 64];
     }
-    if (nsplit > 1) {
-        // partial tile, fp32, row-major [rows][N]: the 32 lanes of a half-wavefront cover 128
-        // contiguous bytes of a row
-        float *dst = part + (size_t)split * rows * N;
+    if (ranges > 1) {
+        // partial tile, fp32: the 32 lanes of a half-wavefront cover 128 contiguous bytes of a row.
+        // Divided problem: [range][rows][N]; divided tail: [tail tile][range][BM][BN].
+        const bool tail = tail_split > 1;
+        float *dst = tail ? part + ((size_t)(tile_id - full_tiles) * tail_split + split) * (BM * BN)
+                          : part + (size_t)split * rows * N;
+        const size_t pitch = tail ? BN : N;
+        const int rbase = tail ? 0 : row0, cbase = tail ? 0 : col0;
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
-            const int col = col0 + wn * TN + j * 32 + rl;
-            if (col >= N) continue;
+            const int lcol = wn * TN + j * 32 + rl;
+            if (col0 + lcol >= N) continue;
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int row = row0 + wm * TM + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                    if (row < rows) dst[(size_t)row * N + col] = acc[i][j][e];
+                    const int lrow = wm * TM + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+                    if (row0 + lrow < rows) dst[(size_t)(rbase + lrow) * pitch + cbase + lcol] = acc[i][j][e];
                 }
         }
         return;
     }
-    // per-wavefront staging region behind the reduction buffer: bf16 tile, or fp32 tile when the
-    // output is fp32 and it fits (epi_lds_bytes() below is what the launcher allocates)
-    constexpr bool F32_STAGED = gemm_f32_staging_fits(BM, BN, WM, WN, KS);
-    constexpr int FE = epi_frags(FM);                     // fragments per epilogue pass
-    constexpr int WREGION = F32_STAGED ? FE * 32 * (TN + 4) * 4 : FE * 32 * (TN + 8) * 2;    // bytes
-    uint16_t *wlds = reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(lds_raw) + RED_FLOATS * 4 +
-                                                  wsub * WREGION);
-    store_tile_epilogue<FE, FN, F32_STAGED>(acc, ep, rows, N, row0 + wm * TM, col0 + wn * TN, lane,
-                                            wlds);
+    // per-wavefront staging region behind the reduction buffer; the sub-tile passes through it a few
+    // fragments at a time (fewer per pass when the output is fp32)
+    constexpr int FE = epi_frags(FM), FE32 = epi_frags_f32(BM, BN, WM, WN, KS);
+    static_assert(gemm_red_bytes(BM, BN, KS) + epi_bytes_f32(BN, WM, WN, FE32) <= kLdsLimit, "fp32 staging");
+    char *stage_base = reinterpret_cast<char *>(lds_raw) + RED_FLOATS * 4;
+    if (ep.out_f32) {
+        uint16_t *wlds = reinterpret_cast<uint16_t *>(stage_base + wsub * (FE32 * 32 * (TN + 4) * 4));
+#pragma unroll
+        for (int f0 = 0; f0 < FM; f0 += FE32) {
+            constexpr int dummy = 0; (void)dummy;
+            if (f0 + FE32 <= FM)
+                store_tile_epilogue<FE32, FN, true>(acc + f0, ep, rows, N, row0 + wm * TM + f0 * 32,
+                                                    col0 + wn * TN, lane, wlds);
+            else
+                store_tile_epilogue<(FM % FE32 ? FM % FE32 : FE32), FN, true>(
+                    acc + f0, ep, rows, N, row0 + wm * TM + f0 * 32, col0 + wn * TN, lane, wlds);
+        }
+        return;
+    }
+    uint16_t *wlds = reinterpret_cast<uint16_t *>(stage_base + wsub * (FE * 32 * (TN + 8) * 2));
+    store_tile_epilogue<FE, FN, false>(acc, ep, rows, N, row0 + wm * TM, col0 + wn * TN, lane, wlds);
     if constexpr (FE < FM)
-        store_tile_epilogue<FM - FE, FN, F32_STAGED>(acc + FE, ep, rows, N, row0 + wm * TM + FE * 32,
-                                                     col0 + wn * TN, lane, wlds);
+        store_tile_epilogue<FM - FE, FN, false>(acc + FE, ep, rows, N, row0 + wm * TM + FE * 32,
+                                                col0 + wn * TN, lane, wlds);
 }
 
+// Sum of the partial tiles of the divided tail + the epilogue (bias, GELU, residual, bf16 or fp32
+// output; never the K/V routing).  One thread per 4 consecutive columns of one tile row.
+__global__ __launch_bounds__(256) void gemm_tail_epilogue_kernel(const float *__restrict__ part,
+                                                                 int ranges, int full_tiles,
+                                                                 int tiles_m, int tiles_n, int group_m,
+                                                                 int BM, int BN, int rows, int N,
+                                                                 long total, EpiParams ep)
+{
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;       // over tail tiles * BM * BN/4
+    if (idx >= total) return;
+    const int cpr = BN / 4;
+    const int lcol = (int)(idx % cpr) * 4;
+    const long tr = idx / cpr;
+    const int lrow = (int)(tr % BM), tt = (int)(tr / BM), pid = full_tiles + tt;
+    const int group = pid / (group_m * tiles_n);
+    const int first_m = group * group_m;
+    const int gsize = min(tiles_m - first_m, group_m);
+    const int tm = first_m + (pid % (group_m * tiles_n)) % gsize;
+    const int tn = (pid % (group_m * tiles_n)) / gsize;
+    const int row = tm * BM + lrow, col = tn * BN + lcol;
+    if (row >= rows || col >= N) return;
+    const float *src = part + (size_t)tt * ranges * BM * BN + (size_t)lrow * BN + lcol;
+    float4 v = *reinterpret_cast<const float4 *>(src);
+    for (int s = 1; s < ranges; ++s) {
+        const float4 p = *reinterpret_cast<const float4 *>(src + (size_t)s * BM * BN);
+        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    if (ep.bias) {
+        const uint2 b = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(ep.bias) + col);
+        v.x += bf16_lo(b.x); v.y += bf16_hi(b.x); v.z += bf16_lo(b.y); v.w += bf16_hi(b.y);
+    }
+    if (ep.gelu) { v.x = gelu_tanh(v.x); v.y = gelu_tanh(v.y); v.z = gelu_tanh(v.z); v.w = gelu_tanh(v.w); }
+    const size_t off = (size_t)row * N + col;
+    if (ep.residual) {
+        if (ep.res_f32) {
+            const float4 r = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(ep.residual) + off);
+            v.x += r.x; v.y += r.y; v.z += r.z; v.w += r.w;
+        } else {
+            const uint2 r = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint16_t *>(ep.residual) + off);
+            v.x += bf16_lo(r.x); v.y += bf16_hi(r.x); v.z += bf16_lo(r.y); v.w += bf16_hi(r.y);
+        }
+    }
+    const size_t ooff = (size_t)row * ep.ld0 + col;
+    if (ep.out_f32)
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(ep.out0) + ooff) = v;
+    else
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(ep.out0) + ooff) =
+            make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+}
+
+// tail > 1: the tiles beyond the last full round of 256 are divided into `tail` ranges of the
+// contraction axis each (nsplit must be 1 then)
 template <int BM, int BN, int WM, int WN, int STAGES, int KS = 1>
 static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, int K,
                                  const EpiParams &ep, hipStream_t st, int nsplit = 1,
-                                 float *part = nullptr)
+                                 float *part = nullptr, int tail = 1)
 {
     const int tiles_m = (rows + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int ntiles = tiles_m * tiles_n;
-    const int grid = (ntiles * nsplit + 7) / 8 * 8;
+    const int full_tiles = tail > 1 ? ntiles / 256 * 256 : ntiles;
+    const int tail_units = (ntiles - full_tiles) * tail;
+    const int grid = tail > 1 ? full_tiles + (tail_units + 7) / 8 * 8 : (ntiles * nsplit + 7) / 8 * 8;
     const size_t lds_stages = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
     const size_t lds_epi = gemm_epi_lds_bytes(BM, BN, WM, WN, KS);
     const size_t lds = lds_stages > lds_epi ? lds_stages : lds_epi;
@@ -432,7 +520,13 @@ static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, 
     int group_m = (int)lround(sqrt((double)ntiles * BN / (8.0 * BM)));
     group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
     launch(kern, dim3(grid), dim3(64 * WM * WN * KS), lds, st, (const uint16_t *)A,
-                       (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, group_m, ep, nsplit, part);
+                       (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, group_m, ep, nsplit, part,
+                       full_tiles, tail);
+    if (tail > 1) {
+        const long total = (long)(ntiles - full_tiles) * BM * (BN / 4);
+        launch(gemm_tail_epilogue_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+               (const float *)part, tail, full_tiles, tiles_m, tiles_n, group_m, BM, BN, rows, N, total, ep);
+    }
 }
 
 // Sum of the partial tiles of a split contraction + the epilogue (bias, GELU, residual, bf16 or
@@ -528,26 +622,47 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 }
 
 // Tile configuration for a problem: rounds of workgroups over the 256 CUs (one workgroup per CU
-// at these LDS sizes) x tile area / sustained rate of the configuration (TFLOP/s measured on large
-// problems).  Returns the index into the table and the number of tiles.
-static int pick_bf16_config(int rows, int N, long *tiles_out)
+// at these LDS sizes) x time of one tile at the sustained rate of the configuration (TFLOP/s
+// measured on large problems).  With `allow_tail` the tiles beyond the last full round may be
+// divided along the contraction axis into 2..8 ranges (each at least 8 k-tiles long) so that
+// they fill the chip once more at a fraction of a tile's time; their fp32 partial tiles cost a
+// write and a read at about 4 TB/s.
+struct GemmPlan { int cfg; long tiles; int tail; size_t tail_floats; };
+static GemmPlan plan_bf16(int rows, int N, int K, bool allow_tail)
 {
     struct Cand { int bm, bn; double rate; };
     const Cand cands[6] = {{256, 256, 1155.0}, {256, 128, 1045.0}, {128, 256, 1041.0},
                            {128, 128, 1000.0}, {320, 256, 1200.0}, {192, 256, 1100.0}};
-    int best = 0;
+    GemmPlan best{0, 0, 1, 0};
     double best_cost = 1e300;
-    long best_tiles = 0;
     for (int i = 0; i < 6; ++i) {
         const long tiles = (long)((rows + cands[i].bm - 1) / cands[i].bm) *
                            ((N + cands[i].bn - 1) / cands[i].bn);
         double rate = cands[i].rate;
         if (i == 3 && tiles > 256) rate = 650.0;       // small tiles pay per round
-        const double cost = (double)((tiles + 255) / 256) * cands[i].bm * cands[i].bn / rate;
-        if (cost < best_cost) { best_cost = cost; best = i; best_tiles = tiles; }
+        const double area = (double)cands[i].bm * cands[i].bn;
+        const double t_tile = 2.0 * area * K * 256.0 / (rate * 1e6);     // microseconds on one CU
+        const double cost = (double)((tiles + 255) / 256) * t_tile;
+        if (cost < best_cost) { best_cost = cost; best = GemmPlan{i, tiles, 1, 0}; }
+        const long full = tiles / 256 * 256, rem = tiles - full;
+        if (!allow_tail || i == 3 || full == 0 || rem == 0) continue;
+        for (int s = 2; s <= 8; ++s) {
+            if (rem * s > 256 || K / BK / s < 8) break;
+            const double c2 = (double)(full / 256) * t_tile + t_tile / s + 10.0 +
+                              (double)rem * s * area * 8.0 / 4e6;
+            if (c2 < best_cost) {
+                best_cost = c2;
+                best = GemmPlan{i, tiles, s, (size_t)rem * s * (size_t)area};
+            }
+        }
     }
-    *tiles_out = best_tiles;
     return best;
+}
+static int pick_bf16_config(int rows, int N, long *tiles_out)
+{
+    const GemmPlan p = plan_bf16(rows, N, BK * 64, false);
+    *tiles_out = p.tiles;
+    return p.cfg;
 }
 
 // Workgroups per tile along the contraction axis: only when the tiles cover at most half of the
@@ -566,6 +681,16 @@ int gemm_splits(DType dt, int rows, int N, int K)
     return (int)((kt + per - 1) / per);                  // no empty part
 }
 
+// Floats of scratch a bf16 linear layer may need for partial tiles (either way of dividing the
+// contraction axis); 0 when every tile is computed by one workgroup.
+size_t gemm_scratch_floats(DType dt, int rows, int N, int K)
+{
+    if (dt != DType::BF16) return 0;
+    const int ns = gemm_splits(dt, rows, N, K);
+    if (ns > 1) return (size_t)ns * rows * N;
+    return plan_bf16(rows, N, K, true).tail_floats;
+}
+
 void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
                  const GemmEpilogue &e, hipStream_t st)
 {
@@ -579,18 +704,20 @@ void launch_gemm(DType dt, const void *A, const void *W, int rows, int N, int K,
     ep.out_f32 = e.out_f32;
     ep.res_f32 = e.res_f32;
     if (dt == DType::BF16) {
-        long tiles;
-        const int best = pick_bf16_config(rows, N, &tiles);
-        // the K/V routing lives in the in-kernel epilogue only, so the routed launch is never split
-        const int ns = (e.splitk_scratch && e.split == N) ? gemm_splits(dt, rows, N, K) : 1;
-        float *part = ns > 1 ? e.splitk_scratch : nullptr;
+        // the K/V routing lives in the in-kernel epilogue only, so the routed launch is never divided
+        const bool may_divide = e.splitk_scratch && e.split == N;
+        const int ns = may_divide ? gemm_splits(dt, rows, N, K) : 1;
+        const GemmPlan plan = plan_bf16(rows, N, K, may_divide && ns == 1);
+        const int best = ns > 1 ? plan_bf16(rows, N, K, false).cfg : plan.cfg;
+        const int tail = ns > 1 ? 1 : plan.tail;
+        float *part = (ns > 1 || tail > 1) ? e.splitk_scratch : nullptr;
         switch (best) {
-        case 0: launch_gemm_bf16_cfg<256, 256, 2, 4, 2>(A, W, rows, N, K, ep, st, ns, part); break;
-        case 1: launch_gemm_bf16_cfg<256, 128, 4, 2, 3>(A, W, rows, N, K, ep, st, ns, part); break;
-        case 2: launch_gemm_bf16_cfg<128, 256, 2, 4, 3>(A, W, rows, N, K, ep, st, ns, part); break;
-        case 4: launch_gemm_bf16_cfg<320, 256, 2, 4, 2>(A, W, rows, N, K, ep, st, ns, part); break;
-        case 5: launch_gemm_bf16_cfg<192, 256, 2, 4, 2>(A, W, rows, N, K, ep, st, ns, part); break;
-        default: launch_gemm_bf16_cfg<128, 128, 2, 2, 3, 2>(A, W, rows, N, K, ep, st, ns, part); break;
+        case 0: launch_gemm_bf16_cfg<256, 256, 2, 4, 2>(A, W, rows, N, K, ep, st, ns, part, tail); break;
+        case 1: launch_gemm_bf16_cfg<256, 128, 4, 2, 3>(A, W, rows, N, K, ep, st, ns, part, tail); break;
+        case 2: launch_gemm_bf16_cfg<128, 256, 2, 4, 3>(A, W, rows, N, K, ep, st, ns, part, tail); break;
+        case 4: launch_gemm_bf16_cfg<320, 256, 2, 4, 2>(A, W, rows, N, K, ep, st, ns, part, tail); break;
+        case 5: launch_gemm_bf16_cfg<192, 256, 2, 4, 2>(A, W, rows, N, K, ep, st, ns, part, tail); break;
+        default: launch_gemm_bf16_cfg<128, 128, 2, 2, 3, 2>(A, W, rows, N, K, ep, st, ns, part, tail); break;
         }
         if (ns > 1) {
             const long total = (long)rows * (N / 4);
