@@ -90,6 +90,28 @@ class Chain:
             x = y
         return x
 
+    def scored_scale(self, side):
+        """The same chain with the scores of block i+1 produced by the kernels that write block
+        i's output map (fvar_lowrank_fill_scored): only the first block of the scale reads its
+        input to score it."""
+        fv, W, s = self.fv, self.W, self.scale[side]
+        B, M, k, r = W.batch, s["M"], s["k"], W.rank
+        if "scores" not in s:
+            s["scores"] = self.torch.empty((B, M), dtype=self.torch.float32, device="cuda")
+            s["fill_ws"] = self.torch.empty(fv.fvar_fill_scored_workspace_bytes(self.ctx, B, M),
+                                            dtype=self.torch.uint8, device="cuda")
+        x = s["x0"]
+        for i, (w, K, V) in enumerate(self.blocks):
+            y = s["bufs"][i & 1]
+            fv.fvar_score_select(self.ctx, x, B, M, k, s["keep"], s["drop"], ws=self.sel_ws,
+                                 scores_in=s["scores"] if i else None)
+            fv.fvar_block_forward_pruned(self.ctx, w, x, B, M, s["keep"], k, K, V, self.cap, s["Lp"],
+                                         s["y_keep"], self.ws)
+            fv.fvar_lowrank_fill_scored(self.ctx, s["y_keep"], s["keep"], s["drop"], B, M, k, r,
+                                        s["Wc"][i], s["Gc"][i], y, s["scores"], s["fill_ws"])
+            x = y
+        return x
+
     def rp_state(self, side):
         """Extra device state of the random-projection input variant and of the factor
         construction: Q^T [k,M] and [r,M] with N(0,1/rows) entries, and a cached counterpart
@@ -175,6 +197,32 @@ class Chain:
         fv.fvar_cache_factors(self.ctx, s["C_all"], s["Qt_r"], False, n, M, r, 0.0, s["W_all"],
                               s["G_all"], s["fws_all"])
 
+    def factored_handover(self, side):
+        """What hands the cached counterpart features to scale `side` in factored form: the
+        outputs of all blocks at the previous scale are factored in one call (batch = blocks x B)
+        and the thin factors are up-sampled to this scale's grid.  Returns the previous side."""
+        import workloads as wl
+        fv, W, torch = self.fv, self.W, self.torch
+        prev = W.scales[W.scales.index(side) - 1]
+        s = self.scale[side]
+        n, Mp, M, r, d = W.batch * W.blocks, prev * prev, side * side, W.rank, W.hidden
+        if "ho" not in s:
+            dt = s["x0"].dtype
+            g = torch.Generator(device="cuda").manual_seed(4200 + side)
+            Wd = __import__("dataclasses").replace(W, batch=n, blocks=0)
+            ho = {"C": wl.device_workload(Wd, prev, seed=5100)[0],
+                  "Qt": (torch.randn((r, Mp), generator=g, device="cuda") / r ** 0.5).to(dt),
+                  "Ws": torch.empty((n, Mp, r), dtype=dt, device="cuda"),
+                  "G": torch.empty((n, r, d), dtype=dt, device="cuda"),
+                  "Wup": torch.empty((n, M, r), dtype=dt, device="cuda"),
+                  "ws": torch.empty(fv.fvar_factors_workspace_bytes(self.ctx, n, Mp, r), dtype=torch.uint8,
+                                    device="cuda")}
+            s["ho"] = ho
+        ho = s["ho"]
+        fv.fvar_cache_factors(self.ctx, ho["C"], ho["Qt"], False, n, Mp, r, 0.0, ho["Ws"], ho["G"], ho["ws"])
+        fv.fvar_upsample_tokens(self.ctx, ho["Ws"], n, prev, prev, r, side, side, ho["Wup"])
+        return prev
+
     def step(self, dense=False, events=None):
         for side in self.W.late_scales:
             if events is not None:
@@ -219,6 +267,38 @@ def kernel_work(W, side):
     return out
 
 
+def handover(chain, W, fv, torch):
+    """Per late scale: time of the factored hand-over of the cached features from the previous
+    scale (factor build of all blocks in one call + up-sampling of the thin factors), per block."""
+    es = 2 if W.dtype == "bf16" else 4
+    rep = {}
+    for side in W.late_scales:
+        if W.scales.index(side) == 0:
+            continue
+        prev = chain.factored_handover(side)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            chain.factored_handover(side)
+        torch.cuda.synchronize()
+        wall_us = (time.perf_counter() - t0) * 1e6 / 3
+        fv.fvar_profile_enable(chain.ctx, True)
+        chain.factored_handover(side)
+        torch.cuda.synchronize()
+        prof = fv.fvar_profile_read(chain.ctx)
+        fv.fvar_profile_enable(chain.ctx, False)
+        n = W.batch * W.blocks
+        up_us = prof["upsample"][1] * 1e3
+        up_bytes = n * (prev * prev + side * side) * W.rank * es
+        rep[str(side)] = {"from_scale": prev, "us_per_block": round(wall_us / W.blocks, 1),
+                          "factor_kernels_us_per_block": {l: round(v[1] * 1e3 / W.blocks, 2)
+                                                          for l, v in prof.items() if l != "upsample"},
+                          "upsample": {"us_all_blocks": round(up_us, 2), "GB/s": round(up_bytes / up_us / 1e3, 1),
+                                       "bytes": up_bytes}}
+        chain.scale[side].pop("ho")
+    return rep
+
+
 def rates(prof, work):
     """{label: avg_us and achieved rate} from a profile read and the per-launch work table."""
     rep = {}
@@ -252,6 +332,22 @@ def variants(chain, W, fv, torch, steps):
             chain.chunked_scale(side)
     torch.cuda.synchronize()
     ms_chunk = (time.perf_counter() - t0) * 1e3 / steps
+    for side in W.late_scales:
+        chain.scored_scale(side)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for side in W.late_scales:
+            chain.scored_scale(side)
+    torch.cuda.synchronize()
+    ms_scored = (time.perf_counter() - t0) * 1e3 / steps
+    fv.fvar_profile_enable(chain.ctx, True)
+    for side in W.late_scales:
+        chain.scored_scale(side)
+    torch.cuda.synchronize()
+    scored_k = {l: round(v[1] * 1e3 / v[0], 2) for l, v in fv.fvar_profile_read(chain.ctx).items()
+                if l in ("score", "select", "fill")}
+    fv.fvar_profile_enable(chain.ctx, False)
     fv.fvar_profile_enable(chain.ctx, True)
     rp_k, fac = {}, {}
     for side in W.late_scales:
@@ -292,8 +388,11 @@ def variants(chain, W, fv, torch, steps):
             chain.scale[side].pop(k)
     return {"selection_per_chunk_of_4_blocks": {"ms_per_step": ms_chunk,
                                                 "tokens_per_s": tokens / (ms_chunk * 1e-3)},
+            "scores_from_the_fill": {"ms_per_step": ms_scored, "tokens_per_s": tokens / (ms_scored * 1e-3),
+                                     "avg_us": scored_k},
             "rp_input_path": {"ms_per_step": ms, "tokens_per_s": tokens / (ms * 1e-3), "kernels": rp_k},
-            "cache_factors": fac}
+            "cache_factors": fac,
+            "factored_cache_handover": handover(chain, W, fv, torch)}
 
 
 def cpu_baseline(W, scales=None, samples=1, budget_gflop=300.0):

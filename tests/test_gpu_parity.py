@@ -150,11 +150,18 @@ def test_lowrank_fill_scored(dtype, r, M, d, k):
         check_scores_of_map(sh[b], yh[b])
         ref = oracle.lowrank_fill(yk[b], keep[b], drop[b], M, Wc[b], Gc[b])
         assert rel_err(yh[b], ref) <= TOL[dtype]
-    # the next block's selection from these scores is the selection from the map itself
+    # the next block's selection from these scores is the oracle's selection on the stored map
     kk = max(1, M // 3)
     s2, keep2, drop2 = blk.score_select(y, kk)
     _, keep3, drop3 = blk.score_select(y, kk, scores_in=scores)
     torch.cuda.synchronize()
+    for b in range(B):
+        ko, do = oracle.topk(sh[b], kk)
+        assert np.array_equal(keep3[b].cpu().numpy(), ko) and np.array_equal(drop3[b].cpu().numpy(), do)
+        so = oracle.scores(yh[b])
+        if np.array_equal(so, sh[b]):
+            k2, d2 = oracle.topk(so, kk)
+            assert np.array_equal(ko, k2) and np.array_equal(do, d2)
     if np.array_equal(to_np(s2), sh):
         assert torch.equal(keep2, keep3) and torch.equal(drop2, drop3)
 

@@ -64,6 +64,11 @@ WORKLOADS: Dict[str, Workload] = {
     # same, batch 16 with classifier-free-guidance doubling (effective batch 32)
     "infinity2b_1024_b32_bf16": Workload("infinity2b_1024_b32_bf16", 2048, 16, 128, 8192, _INF,
                                          (40, 48, 64), 3, 10, 64, 32, 32, "bf16"),
+    # STAR-1.7B-shaped: 30 blocks, the reduction applied at the 64x64 scale only (the paper's
+    # setting for that model); block geometry assumed from the parameter count (1.7e9 / 30 blocks
+    # / 12 d^2 gives d close to 2048), keep ratio = the paper's mean rank fraction 17.6 %
+    "star_shaped_1024_bf16": Workload("star_shaped_1024_bf16", 2048, 16, 128, 8192, _INF,
+                                      (64,), 22, 125, 64, 4, 30, "bf16"),
     # large-model shape with an extra 80x80 final scale
     "large_1280_bf16": Workload("large_1280_bf16", 4096, 32, 128, 16384, _INF + (80,),
                                 (80,), 1, 4, 128, 4, 40, "bf16"),
