@@ -57,6 +57,14 @@ template <int DH> __device__ __forceinline__ int v_swz(int row)
     return DH == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
 
+// Position of workgroup `id` of `count` in a numbering that gives XCD x (= id % 8) the x-th
+// contiguous share of [0, count): a bijection for any count.
+__device__ __forceinline__ int xcd_contiguous(int id, int count)
+{
+    const int x = id & 7, pos = id >> 3, q = count >> 3, r = count & 7;
+    return (x < r ? x * (q + 1) : r * (q + 1) + (x - r) * q) + pos;
+}
+
 template <int DH, int NQ>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__restrict__ q,
                                                         const uint16_t *__restrict__ Kc,
@@ -91,16 +99,24 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *__res
     //    ranges.
     // A workgroup with a partial key range [tile0, tile1) leaves an unnormalised partial result
     // (O, running max, running sum) for a merge kernel.
+    // Workgroups are handed to the 8 XCDs in turn (id % 8), each with an L2 of its own, so ids
+    // are first renumbered to give every XCD one contiguous run of the numbering above: the query
+    // blocks of a head, which stream the same keys and values, then share one L2 instead of
+    // fetching them from memory once per XCD.  Whole units and the divided last round are
+    // renumbered separately, so the last round is still made of the short pieces on every XCD.
     int unit = blockIdx.x, split = 0, ranges = 1;
     size_t prow_base = 0;                                    // partial row of query 0 of this unit
     int prow_stride = 0;
     if (nsplit > 1) {
+        unit = xcd_contiguous(unit, (int)gridDim.x);
         const int per = H * nqb, zz = unit / per;
         split = zz % nsplit;
         ranges = nsplit;
         unit = (zz / nsplit) * per + unit % per;
-    } else if (unit >= full_units) {
-        const int t = unit - full_units;
+    } else if (unit < full_units) {
+        unit = xcd_contiguous(unit, full_units);
+    } else {
+        const int t = xcd_contiguous(unit - full_units, (int)gridDim.x - full_units);
         unit = full_units + t / tail_split;
         split = t % tail_split;
         ranges = tail_split;
