@@ -27,7 +27,12 @@ WORKLOAD = "large_1280_bf16"
 # each scaled by what the same counter reads for a device copy of known size; the summary file
 # under profiles/ is named in the entry).  An entry is dropped (traffic: null) whenever gemm.hip
 # changes, until the counters are taken again.
-GEMM_TRAFFIC = {}
+GEMM_TRAFFIC = {
+    "large_1280_bf16": {"bytes_per_launch": 1.422e9,
+                        "source": "profiles/pruned_chain_large_1280_bf16_hbm_counters.txt"},
+    "infinity2b_1024_b32_bf16": {"bytes_per_launch": 1.781e9,
+                                 "source": "profiles/pruned_chain_infinity2b_1024_b32_bf16_hbm_counters.txt"},
+}
 SWEEP_WORKLOAD = "infinity2b_1024_b32_bf16"
 
 
@@ -558,6 +563,11 @@ def main():
     ap.add_argument("--rank", type=int, default=None, help="fill rank instead of the workload's")
     ap.add_argument("--sweep", action="store_true",
                     help=f"keep-ratio x rank x scale table of {SWEEP_WORKLOAD} instead of one workload")
+    ap.add_argument("--constant-operands", action="store_true",
+                    help="overwrite every input, weight, cache and factor with the constant 1.0 "
+                         "before timing: same launches and flop counts on operands that toggle no "
+                         "bits, which shows how much of the step time is the chip's clock governor "
+                         "(the line says data: constant and is no throughput figure)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB device copy (reference for scaling HBM counters)")
     args = ap.parse_args()
@@ -597,6 +607,14 @@ def main():
         W = dataclasses.replace(W, keep_num=num, keep_den=den, rank=args.rank or W.rank)
         default_wl = False
     chain = Chain(W, fv, torch)
+    if args.constant_operands:
+        default_wl = False
+        for w, K, V in chain.blocks:
+            for t in list(w.values()) + [K, V]:
+                t.fill_(1.0)
+        for s in chain.scale.values():
+            for t in [s["x0"]] + list(s["Wc"]) + list(s["Gc"]):
+                t.fill_(1.0)
 
     if args.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_()
@@ -606,6 +624,8 @@ def main():
     m = measure(chain, W, fv, torch, args.steps, args.warmup, with_dense=not args.no_dense)
     ms_per_step, tokens, dense = m["ms_per_step"], m["tokens"], m["dense"]
     traffic = GEMM_TRAFFIC.get(args.workload) if not (args.keep or args.rank) else None
+    if args.constant_operands:
+        traffic = None
     if traffic:
         m["roofline"]["traffic"] = traffic["bytes_per_launch"]
         m["roofline"]["traffic_source"] = traffic["source"]
@@ -615,7 +635,7 @@ def main():
         "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": W.dtype,
-        "data": "synthetic",
+        "data": "constant" if args.constant_operands else "synthetic",
         "config": {"workload": args.workload, "hidden": W.hidden, "heads": W.heads,
                    "head_dim": W.head_dim, "blocks": W.blocks, "batch": W.batch,
                    "late_scales": list(W.late_scales), "keep_ratio": W.keep_num / W.keep_den,
