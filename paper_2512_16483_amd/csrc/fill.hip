@@ -142,24 +142,34 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(const uint16_t *__restri
     int grp_row = share * 4 + wave;                             // this wavefront's current group
 
     // other operand: lane (row rl, half g) holds w_c[row][16s + 8g .. +8)
+    // The token row of a slot comes from idx_drop: that index is fetched two groups ahead of the
+    // MFMAs (one group ahead of the w_c fragments it addresses), so neither the fragment loads nor
+    // the stores wait for an index at the moment they are issued.
     uint4 afrag[2][KSTEPS];
-    auto load_a = [&](int grpi, uint4 *dst) {
-        const int slot = min(grpi * 32 + rl, nd - 1);
-        const uint16_t *wrow = W + (size_t)drop[slot] * r;
+    auto load_row = [&](int grpi) { return drop[min(grpi * 32 + rl, nd - 1)]; };
+    auto load_a = [&](int row, uint4 *dst) {
+        const uint16_t *wrow = W + (size_t)row * r;
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {
             const int t = 16 * s + 8 * g;
             dst[s] = t < r ? *reinterpret_cast<const uint4 *>(wrow + t) : make_uint4(0, 0, 0, 0);
         }
     };
-    if (grp_row < groups) load_a(grp_row, afrag[0]);
+    int row_next = 0;                                          // token row of this lane in the next group
+    if (grp_row < groups) load_a(load_row(grp_row), afrag[0]);
+    if (grp_row + gstep < groups) row_next = load_row(grp_row + gstep);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     // one 32-row group: af holds its w_c fragments, af_next receives those of the next group
     auto group = [&](int grp_row, const uint4 *af, uint4 *af_next) {
         const int j0 = grp_row * 32;
-        if (grp_row + gstep < groups) load_a(grp_row + gstep, af_next);
+        // destination rows of the 4 row-chunks this lane stores per half (rows it*8 + lane/8)
+        int orow[4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) orow[it] = drop[min(j0 + it * 8 + (lane >> 3), nd - 1)];
+        if (grp_row + gstep < groups) load_a(row_next, af_next);
+        if (grp_row + 2 * gstep < groups) row_next = load_row(grp_row + 2 * gstep);
         double erow[4] = {0.0, 0.0, 0.0, 0.0};
         // two halves of 64 columns: 2 x 32-column accumulator tiles each
 #pragma unroll 1
@@ -204,7 +214,7 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(const uint16_t *__restri
                 const uint4 v = *reinterpret_cast<const uint4 *>(wl + lrow * kFillStage + c);
                 const int col = col0 + half * 64 + c;
                 const bool ok = rr < nd && col < d;
-                if (ok) *reinterpret_cast<uint4 *>(Y + (size_t)drop[rr] * d + col) = v;
+                if (ok) *reinterpret_cast<uint4 *>(Y + (size_t)orow[it] * d + col) = v;
                 if (parts && ok) erow[it] += chunk_energy<uint16_t>(v);
             }
             asm volatile("" ::: "memory");
@@ -220,7 +230,7 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(const uint16_t *__restri
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 const int rr = j0 + it * 8 + (lane >> 3);
-                if (rr < nd) parts[((size_t)b * M + drop[rr]) * slabs + slab] = e8[it];
+                if (rr < nd) parts[((size_t)b * M + orow[it]) * slabs + slab] = e8[it];
             }
         }
     };
