@@ -2,10 +2,11 @@
 // MLP): C = epilogue(A[rows,K] * W[N,K]^T).  Both operands are K-contiguous ("out,in" weights),
 // which is the layout the MFMA operands want: a lane holds 8 consecutive k of one row.
 //
-// bf16: workgroup tile BM x BN x 64 computed by WM x WN wavefronts with v_mfma_f32_32x32x16_bf16
-// (fp32 accumulation).  Tiles are DMA-ed global -> LDS (no register staging) into a ring of
-// stages ahead of the MFMAs; operand fragments are read one 16-wide k-step ahead of the MFMAs
-// that use them.  LDS rows are 128 B; the 16-byte chunk index is XOR-swizzled with (row/2)%8 so
+// bf16: workgroup tile BM x BN x 64 computed by WM x WN wavefronts with v_mfma_f32_16x16x32_bf16
+// (fp32 accumulation; on operands with realistic bit activity the chip sustains a higher clock
+// on this shape than on 32x32x16: half the accumulator register traffic per flop).  Tiles are
+// DMA-ed global -> LDS (no register staging) into a ring of stages ahead of the MFMAs; operand
+// fragments are read from LDS a few MFMA groups ahead of their use.  LDS rows are 128 B; the 16-byte chunk index is XOR-swizzled with (row/2)%8 so
 // that the ds_read_b128 operand fetches of 16 consecutive rows cover all 64 banks exactly once.
 // Workgroup ids are remapped so that each XCD (own L2) works on a compact patch of the tile
 // grid.  Bigger tiles cut the L1/LDS traffic per flop (a 128x128 tile needs the full 64 B/clk of
@@ -63,20 +64,21 @@ __device__ __forceinline__ int lds_off(int row, int chunk)      // in bf16 eleme
     return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3);
 }
 
-// Epilogue of the bf16 kernel.  Accumulator entry e of a 32x32 tile holds row
-// 8*(e/4) + 4*(lane/32) + e%4, column lane%32.  Each wavefront applies bias and GELU, packs to
+// Epilogue of the bf16 kernel.  The accumulators of a wavefront are kept per 32x32 region
+// [i][j] as 2x2 blocks [bi][bj] of the 16x16 MFMA: entry e of a block holds row
+// 16*bi + 4*(lane/16) + e, column 16*bj + lane%16 of the region.  Each wavefront applies bias and GELU, packs to
 // bf16 (adjacent lanes swap one value per row pair so that a lane owns two neighbouring columns)
 // and parks its sub-tile row-major in a private LDS region; it then reads the sub-tile back as
 // 16-byte row chunks, adds the residual (16-byte loads) and stores 16 bytes per lane, so a store
 // instruction covers whole 128-byte row segments.  The destination row pointers (plain output,
 // or the K / V cache rows of the sample the row belongs to) are computed once per chunk.
 template <int FM, int FN, bool F32_STAGED>
-__device__ __forceinline__ void store_tile_epilogue(const floatx16_t (*acc)[FN], const EpiParams &ep,
+__device__ __forceinline__ void store_tile_epilogue(const floatx4_t (*acc)[FN][2][2], const EpiParams &ep,
                                                     int rows, int N, int wrow0, int wcol0, int lane,
                                                     uint16_t *wlds)
 {
     constexpr int TM = FM * 32, TN = FN * 32, PITCH = TN + 8;
-    const int rl = lane & 31, g = lane >> 5;
+    const int c16 = lane & 15, q16 = lane >> 4;
     const uint16_t *bias = reinterpret_cast<const uint16_t *>(ep.bias);
     if constexpr (F32_STAGED) {
         // fp32 output (never routed, never GELU-ed; the residual operand is bf16): same two-phase
@@ -86,14 +88,15 @@ __device__ __forceinline__ void store_tile_epilogue(const floatx16_t (*acc)[FN],
         constexpr int P32 = TN + 4;
         float *w32 = reinterpret_cast<float *>(wlds);
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int col = wcol0 + j * 32 + rl;
+        for (int jj = 0; jj < 2 * FN; ++jj) {
+            const int j = jj >> 1, bj = jj & 1;
+            const int col = wcol0 + jj * 16 + c16;
             const float bv = (bias && col < N) ? bf16_to_f32(bias[col]) : 0.f;
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+            for (int ii = 0; ii < 2 * FM; ++ii)
 #pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    w32[(i * 32 + 8 * (e >> 2) + 4 * g + (e & 3)) * P32 + j * 32 + rl] = acc[i][j][e] + bv;
+                for (int e = 0; e < 4; ++e)
+                    w32[(ii * 16 + 4 * q16 + e) * P32 + jj * 16 + c16] = acc[ii >> 1][j][ii & 1][bj][e] + bv;
         }
         asm volatile("" ::: "memory");       // staging stores and loads use different vector types
         constexpr int CPR = TN / 4, RPI = 64 / CPR;
@@ -114,19 +117,20 @@ __device__ __forceinline__ void store_tile_epilogue(const floatx16_t (*acc)[FN],
     }
     const int odd = lane & 1;
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-        const int col = wcol0 + j * 32 + rl;
+    for (int jj = 0; jj < 2 * FN; ++jj) {
+        const int j = jj >> 1, bj = jj & 1;
+        const int col = wcol0 + jj * 16 + c16;
         const float bv = (bias && col < N) ? bf16_to_f32(bias[col]) : 0.f;
-        const int lcol = j * 32 + rl - odd;                  // even column of the stored pair
+        const int lcol = jj * 16 + c16 - odd;                // even column of the stored pair
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
+        for (int ii = 0; ii < 2 * FM; ++ii) {
 #pragma unroll
-            for (int e = 0; e < 16; e += 2) {
-                float v0 = acc[i][j][e] + bv, v1 = acc[i][j][e + 1] + bv;
+            for (int e = 0; e < 4; e += 2) {
+                float v0 = acc[ii >> 1][j][ii & 1][bj][e] + bv, v1 = acc[ii >> 1][j][ii & 1][bj][e + 1] + bv;
                 if (ep.gelu) { v0 = gelu_tanh(v0); v1 = gelu_tanh(v1); }
                 const float send = odd ? v0 : v1;
                 const float recv = __shfl_xor(send, 1);
-                const int lrow = i * 32 + 8 * (e >> 2) + 4 * g + (e & 3) + odd;
+                const int lrow = ii * 16 + 4 * q16 + e + odd;
                 *reinterpret_cast<uint32_t *>(wlds + lrow * PITCH + lcol) =
                     odd ? pack_bf16x2(recv, v1) : pack_bf16x2(v0, recv);
             }
@@ -219,7 +223,7 @@ constexpr size_t gemm_epi_lds_bytes(int BM, int BN, int WM, int WN, int KS)
     return gemm_red_bytes(BM, BN, KS) + (a > b ? a : b);
 }
 
-// KS > 1 splits every k-tile between KS groups of WM x WN wavefronts (group ks takes the 16-wide
+// KS > 1 splits every k-tile between KS groups of WM x WN wavefronts (group ks takes the 32-wide
 // k-steps ks, ks+KS, ...); the groups' partial accumulators are summed through LDS before the
 // epilogue.  This doubles the wavefronts per CU for problems that give a CU only one small tile.
 template <int BM, int BN, int WM, int WN, int STAGES, int KS>
@@ -282,7 +286,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int rl = lane & 31, g = lane >> 5;
+    const int c16 = lane & 15, q16 = lane >> 4;
     const int ks = wave / (WM * WN), wsub = wave % (WM * WN);
     const int wm = wsub / WN, wn = wsub % WN;
 
@@ -314,67 +318,90 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
         for (int i = 0; i < NGB; ++i) dma_b128(W + koff, b_off[i], sbase + BM * BK * 2 + i * (NW * 1024));
     };
 
-    floatx16_t acc[FM][FN];
+    floatx4_t acc[FM][FN][2][2];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = floatx16_t{0};
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[i][j][b >> 1][b & 1] = floatx4_t{0};
 
     const uint16_t *lds = reinterpret_cast<const uint16_t *>(lds_raw);
-    auto load_frags = [&](const uint16_t *tile, int kk, bf16x8_t *a, bf16x8_t *b) {
+    // Operand fragments (16x16x32 MFMA: lane l holds row l%16, k-values 8*(l/16) .. +7 of a 32-wide
+    // k-step).  The MFMAs of a k-tile are walked as ROWS = steps x (TM/16) "rows": one A fragment
+    // (16 tile rows) against the FN16 B fragments of its k-step.  A fragments go through a ring of
+    // four slots filled three rows ahead of their use; the B fragments of a k-step are double
+    // buffered.  The ring runs across k-tiles: the hand-over point of the loop (DMA of k-tile kt+1
+    // landed, barrier) sits three rows before the end of k-tile kt, by which time every wavefront
+    // holds all fragments of k-tile kt in registers, so the same barrier frees that tile's stage
+    // for the DMA of k-tile kt+STAGES.
+    constexpr int FM16 = TM / 16, FN16 = TN / 16;
+    constexpr int SPW = BK / 32 / KS;                    // k-steps of this wavefront per k-tile
+    constexpr int ROWS = SPW * FM16;
+    static_assert(ROWS % 4 == 0 && ROWS >= 4, "ring of four A fragments");
+    static_assert(STAGES == 2 || STAGES == 3, "wait counts below are written for 2 or 3 stages");
+    auto load_a = [&](const uint16_t *tile, int row) {   // row of the walk -> fragment
+        const int q = row / FM16, i = row % FM16;
+        const int r = wm * TM + i * 16 + c16;
+        return *reinterpret_cast<const bf16x8_t *>(tile + lds_off(r, (q * KS + ks) * 4 + q16));
+    };
+    auto load_b = [&](const uint16_t *tile, int q, bf16x8_t *b) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int r = wm * TM + i * 32 + rl;
-            a[i] = *reinterpret_cast<const bf16x8_t *>(tile + lds_off(r, kk * 2 + g));
-        }
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int r = wn * TN + j * 32 + rl;
-            b[j] = *reinterpret_cast<const bf16x8_t *>(tile + BM * BK + lds_off(r, kk * 2 + g));
+        for (int j = 0; j < FN16; ++j) {
+            const int r = wn * TN + j * 16 + c16;
+            b[j] = *reinterpret_cast<const bf16x8_t *>(tile + BM * BK + lds_off(r, (q * KS + ks) * 4 + q16));
         }
     };
 
-    // prologue: STAGES-1 tiles in flight, the first one landed
     issue(0, 0);
-    if (STAGES == 3 && ktiles > 1) {
-        issue(1, 1);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG) : "memory");
-    } else {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
+    if (ktiles > 1) issue(1, 1);
+    if (STAGES == 3 && ktiles > 2) issue(2, 2);
+    if (ktiles == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (STAGES == 3 && ktiles > 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NG) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG) : "memory");
     __syncthreads();
 
-    static_assert(STAGES == 2 || STAGES == 3, "wait counts below are written for 2 or 3 stages");
+    bf16x8_t ring[4], bb[2][FN16];
+    load_b(lds, 0, bb[0]);
+#pragma unroll
+    for (int t = 0; t < 3; ++t) ring[t] = load_a(lds, t);
     int stage = 0;                                       // stage holding k-tile kt
     for (int kt = 0; kt < ktiles; ++kt) {
-        int wstage = stage + STAGES - 1;
-        if (wstage >= STAGES) wstage -= STAGES;
-        const bool ahead = kt + STAGES - 1 < ktiles;     // uniform
-        if (ahead) issue(kt + STAGES - 1, wstage);       // that stage was read in iteration kt-1
-        __builtin_amdgcn_sched_barrier(0);
         const uint16_t *cur = lds + stage * (STAGE_BYTES / 2);
-        constexpr int STEPS = BK / 16 / KS;               // k-steps of this wavefront per k-tile
-        bf16x8_t af[2][FM], bfr[2][FN];
-        load_frags(cur, ks, af[0], bfr[0]);
+        const int nstage = stage + 1 == STAGES ? 0 : stage + 1;
+        const uint16_t *nxt = lds + nstage * (STAGE_BYTES / 2);
+        const bool more = kt + 1 < ktiles;               // uniform
 #pragma unroll
-        for (int q = 0; q < STEPS; ++q) {
-            if (q + 1 < STEPS)
-                load_frags(cur, (q + 1) * KS + ks, af[(q + 1) & 1], bfr[(q + 1) & 1]);
+        for (int row = 0; row < ROWS; ++row) {
+            const int q = row / FM16, i = row % FM16;
+            if (row == ROWS - 3 && more) {
+                // own reads of this stage are complete before the barrier says so
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                // k-tile kt+1 has landed once only the requests of the tiles after it are outstanding
+                if (STAGES == 3 && kt + 2 < ktiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (kt + STAGES < ktiles) issue(kt + STAGES, stage);
+                if (SPW % 2 == 0) load_b(nxt, 0, bb[0]);
+            }
+            if (row + 3 < ROWS) ring[(row + 3) & 3] = load_a(cur, row + 3);
+            else if (more) ring[(row + 3) & 3] = load_a(nxt, row + 3 - ROWS);
+            // B fragments of the next k-step of this tile, fetched in the middle of the current one
+            if (i == FM16 / 2 && q + 1 < SPW) load_b(cur, q + 1, bb[(q + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[q & 1][i], bfr[q & 1][j],
-                                                                        acc[i][j], 0, 0, 0);
+            for (int j = 0; j < FN16; ++j)
+                acc[i >> 1][j >> 1][i & 1][j & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    ring[row & 3], bb[q & 1][j], acc[i >> 1][j >> 1][i & 1][j & 1], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-        // k-tile kt+1 has landed once only the requests of the tiles after it are outstanding
-        if (STAGES == 3 && ahead) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        stage = stage + 1 == STAGES ? 0 : stage + 1;
+        // with an odd number of k-steps per tile the first B buffer is in use until the tile's end
+        if (SPW % 2 == 1 && more) load_b(nxt, 0, bb[0]);
+        stage = nstage;
     }
+    // the stage buffers are reused below: every wavefront must be past its last operand read
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();
     // every request has landed and every wavefront is past its last operand read (barrier above):
     // the stage buffers are free for the k-split reduction and the epilogue's staging
     constexpr int RED_FLOATS = KS > 1 ? WM * WN * FM * FN * 16 * 64 : 0;
@@ -387,7 +414,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) red[((i * FN + j) * 16 + e) * 64] = acc[i][j][e];
+                    for (int e = 0; e < 16; ++e) red[((i * FN + j) * 16 + e) * 64] = acc[i][j][(e >> 3) & 1][(e >> 2) & 1][e & 3];
         }
         __syncthreads();
         if (ks != 0) return;
@@ -396,7 +423,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] += red[((i * FN + j) * 16 + e) * 64];
+                for (int e = 0; e < 16; ++e) acc[i][j][(e >> 3) & 1][(e >> 2) & 1][e & 3] += red[((i * FN + j) * 16 + e) * 64];
     }
     if (ranges > 1) {
         // partial tile, fp32: the 32 lanes of a half-wavefront cover 128 contiguous bytes of a row.
@@ -407,15 +434,16 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
         const size_t pitch = tail ? BN : N;
         const int rbase = tail ? 0 : row0, cbase = tail ? 0 : col0;
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int lcol = wn * TN + j * 32 + rl;
+        for (int jj = 0; jj < 2 * FN; ++jj) {
+            const int lcol = wn * TN + jj * 16 + c16;
             if (col0 + lcol >= N) continue;
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+            for (int ii = 0; ii < 2 * FM; ++ii)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int lrow = wm * TM + i * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                    if (row0 + lrow < rows) dst[(size_t)(rbase + lrow) * pitch + cbase + lcol] = acc[i][j][e];
+                for (int e = 0; e < 4; ++e) {
+                    const int lrow = wm * TM + ii * 16 + 4 * q16 + e;
+                    if (row0 + lrow < rows)
+                        dst[(size_t)(rbase + lrow) * pitch + cbase + lcol] = acc[ii >> 1][jj >> 1][ii & 1][jj & 1][e];
                 }
         }
         return;
