@@ -660,7 +660,7 @@ static GemmPlan plan_bf16(int rows, int N, int K, bool allow_tail)
 {
     struct Cand { int bm, bn; double rate; };
     const Cand cands[6] = {{256, 256, 1155.0}, {256, 128, 1045.0}, {128, 256, 1041.0},
-                           {128, 128, 1000.0}, {320, 256, 1200.0}, {192, 256, 1100.0}};
+                           {128, 128, 1000.0}, {320, 256, 1300.0}, {192, 256, 1100.0}};
     GemmPlan best{0, 0, 1, 0};
     double best_cost = 1e300;
     for (int i = 0; i < 6; ++i) {
