@@ -309,6 +309,18 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     const int ktiles_all = K / BK, kper = (ktiles_all + ranges - 1) / ranges;
     const int kt0 = split * kper;
     const int ktiles = min(ktiles_all, kt0 + kper) - kt0;   // k-tiles of this workgroup (>= 1)
+    // DMA instructions i0 .. i1-1 (of the NG that make up a k-tile) of k-tile kt into `stage`
+    auto issue_part = [&](int kt, int stage, int i0, int i1) {
+        const int koff = (kt0 + kt) * BK;
+        const uint32_t sbase = lds_base + stage * STAGE_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < NGA; ++i)
+            if (i >= i0 && i < i1) dma_b128(A + koff, a_off[i], sbase + i * (NW * 1024));
+#pragma unroll
+        for (int i = 0; i < NGB; ++i)
+            if (NGA + i >= i0 && NGA + i < i1)
+                dma_b128(W + koff, b_off[i], sbase + BM * BK * 2 + i * (NW * 1024));
+    };
     auto issue = [&](int kt, int stage) {               // DMA of this workgroup's k-tile kt into `stage`
         const int koff = (kt0 + kt) * BK;
         const uint32_t sbase = lds_base + stage * STAGE_BYTES + wave * 1024;
@@ -339,6 +351,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     constexpr int SPW = BK / 32 / KS;                    // k-steps of this wavefront per k-tile
     constexpr int ROWS = SPW * FM16;
     static_assert(ROWS % 4 == 0 && ROWS >= 4, "ring of four A fragments");
+    constexpr int SPREAD = ROWS >= 12 ? 6 : 1;           // rows over which a k-tile's DMA is issued
     static_assert(STAGES == 2 || STAGES == 3, "wait counts below are written for 2 or 3 stages");
     auto load_a = [&](const uint16_t *tile, int row) {   // row of the walk -> fragment
         const int q = row / FM16, i = row % FM16;
@@ -381,8 +394,21 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
                 if (STAGES == 3 && kt + 2 < ktiles) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NG) : "memory");
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __syncthreads();
-                if (kt + STAGES < ktiles) issue(kt + STAGES, stage);
                 if (SPW % 2 == 0) load_b(nxt, 0, bb[0]);
+            }
+            // The DMA of k-tile kt+STAGES into the stage that the hand-over frees is issued a few
+            // instructions per row over the SPREAD rows that follow the hand-over (they run into
+            // the next k-tile): a burst of all NG instructions from all wavefronts at once fills
+            // the CU's vector-memory queue and holds up the MFMAs queued behind them.
+            if (row >= ROWS - 3) {
+                const int w = row - (ROWS - 3);
+                if (w < SPREAD && more && kt + STAGES < ktiles)
+                    issue_part(kt + STAGES, stage, w * NG / SPREAD, (w + 1) * NG / SPREAD);
+            } else if (row + 3 < SPREAD) {
+                const int w = row + 3;
+                if (kt >= 1 && kt - 1 + STAGES < ktiles)
+                    issue_part(kt - 1 + STAGES, stage == 0 ? STAGES - 1 : stage - 1, w * NG / SPREAD,
+                               (w + 1) * NG / SPREAD);
             }
             if (row + 3 < ROWS) ring[(row + 3) & 3] = load_a(cur, row + 3);
             else if (more) ring[(row + 3) & 3] = load_a(nxt, row + 3 - ROWS);
