@@ -180,6 +180,11 @@ SMALL = [  # dtype, B, M, d, H, F, Lp, k, r
     ("bf16", 1, 160, 256, 2, 512, 1500, 64, 16),     # batch 1, long cache: key axis split 5 ways (head_dim 128)
     ("bf16", 1, 300, 128, 2, 256, 1000, 150, 16),    # the same with head_dim 64 and two query blocks per wavefront
     ("bf16", 1, 256, 1024, 16, 4096, 424, 128, 32),  # few tiles, long contraction: linear layers split along k
+    # many rows, wide MLP, contraction of one, two and three 64-wide k-tiles: the big-tile GEMM
+    # configurations with a pipeline shorter than their ring of stages
+    ("bf16", 2, 1600, 64, 1, 2048, 10, 1500, 8),
+    ("bf16", 2, 1600, 128, 1, 3072, 10, 1500, 8),
+    ("bf16", 2, 1400, 192, 3, 2304, 70, 1300, 8),
 ]
 
 
