@@ -64,6 +64,15 @@ __device__ __forceinline__ int lds_off(int row, int chunk)      // in bf16 eleme
     return row * BK + ((chunk ^ ((row >> 1) & 7)) << 3);
 }
 
+// Chunk swizzle of a k-major operand tile (rows = k, 256 or 512 bytes each, all starting at the
+// same bank).  The transposing load reads, per 32 lanes, the rows {0..3, 8..11} (or {4..7,
+// 12..15}) + 16n, 32 contiguous bytes of each: the 8 rows go to 8 different 32-byte eighths of the
+// 256-byte bank span.
+__device__ __forceinline__ int bkm_swz(int row)
+{
+    return ((row & 3) | (((row >> 3) & 1) << 2)) << 1;
+}
+
 // Epilogue of the bf16 kernel.  The accumulators of a wavefront are kept per 32x32 region
 // [i][j] as 2x2 blocks [bi][bj] of the 16x16 MFMA: entry e of a block holds row
 // 16*bi + 4*(lane/16) + e, column 16*bj + lane%16 of the region.  Each wavefront applies bias and GELU, packs to
@@ -226,12 +235,21 @@ constexpr size_t gemm_epi_lds_bytes(int BM, int BN, int WM, int WN, int KS)
 // KS > 1 splits every k-tile between KS groups of WM x WN wavefronts (group ks takes the 32-wide
 // k-steps ks, ks+KS, ...); the groups' partial accumulators are summed through LDS before the
 // epilogue.  This doubles the wavefronts per CU for problems that give a CU only one small tile.
-template <int BM, int BN, int WM, int WN, int STAGES, int KS>
+//
+// BKM ("B k-major"): the second operand is given as X[K][N] (row = contraction index, as a token
+// map is when the contraction runs over tokens: paper, Sec. "Random Projection (RP) for Low-Rank
+// Feature", Q^T X) instead of W[N][K].  Its tiles travel to LDS in their own row-major layout and
+// the B fragments come from the transposing LDS load.  This mode runs `nbatch` independent
+// problems of one shape in one launch (operands and output `*_bstride` elements apart), whole
+// tiles only (no division of the contraction), K a multiple of 64 and N a multiple of 8.
+template <int BM, int BN, int WM, int WN, int STAGES, int KS, bool BKM = false>
 __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
-    const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, int rows, int N, int K,
+    const uint16_t *__restrict__ A_in, const uint16_t *__restrict__ W_in, int rows, int N, int K,
     int tiles_m, int tiles_n, int group_m, EpiParams ep, int nsplit, float *__restrict__ part,
-    int full_tiles, int tail_split)
+    int full_tiles, int tail_split, int nbatch, size_t a_bstride, size_t w_bstride,
+    size_t o_bstride)
 {
+    const uint16_t *A = A_in, *W = W_in;
     constexpr int NW = WM * WN * KS;                   // wavefronts per workgroup
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int FM = TM / 32, FN = TN / 32;
@@ -251,7 +269,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     //    workgroups whose partial tiles go to `part` tile by tile; every XCD gets an eighth of
     //    the whole tiles first and an eighth of the divided ones after them.
     // Partial tiles are summed and finished by a second kernel.
-    const int ntiles = tiles_m * tiles_n;
+    const int ntiles = tiles_m * tiles_n * (BKM ? nbatch : 1);
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
     int pid, split = 0, ranges = 1;
     if (tail_split > 1) {
@@ -275,6 +293,13 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
         ranges = nsplit;
     }
     const int tile_id = pid;
+    if (BKM) {
+        const int per = tiles_m * tiles_n, bidx = pid / per;
+        pid -= bidx * per;
+        A += (size_t)bidx * a_bstride;
+        W += (size_t)bidx * w_bstride;
+        ep.out0 = reinterpret_cast<uint16_t *>(ep.out0) + (size_t)bidx * o_bstride;
+    }
     // consecutive tile ids run down group_m row tiles, then across the columns: the contiguous
     // id range of one XCD is a patch of about group_m x (tiles/8/group_m) tiles
     const int group = pid / (group_m * tiles_n);
@@ -302,9 +327,18 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     }
 #pragma unroll
     for (int i = 0; i < NGB; ++i) {
-        const int r = (wave + NW * i) * 8 + (lane >> 3);
-        const int c = (lane & 7) ^ ((r >> 1) & 7);
-        b_off[i] = (uint32_t)(((size_t)min(col0 + r, N - 1) * K + c * 8) * sizeof(uint16_t));
+        if (BKM) {
+            // k-major tile [BK][BN]: a 1 KiB instruction fills 1024 / (2 BN) whole k-rows; lane l
+            // fills physical chunk l % (BN/8) of its row with the logical chunk the swizzle maps there
+            constexpr int CPR = BN / 8, RPI = 64 / CPR;
+            const int r = (wave + NW * i) * RPI + lane / CPR;
+            const int c = (lane % CPR) ^ bkm_swz(r);
+            b_off[i] = (uint32_t)(((size_t)r * N + min(col0 + c * 8, N - 8)) * sizeof(uint16_t));
+        } else {
+            const int r = (wave + NW * i) * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ ((r >> 1) & 7);
+            b_off[i] = (uint32_t)(((size_t)min(col0 + r, N - 1) * K + c * 8) * sizeof(uint16_t));
+        }
     }
     const int ktiles_all = K / BK, kper = (ktiles_all + ranges - 1) / ranges;
     const int kt0 = split * kper;
@@ -319,16 +353,11 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
 #pragma unroll
         for (int i = 0; i < NGB; ++i)
             if (NGA + i >= i0 && NGA + i < i1)
-                dma_b128(W + koff, b_off[i], sbase + BM * BK * 2 + i * (NW * 1024));
+                dma_b128(BKM ? W + (size_t)koff * N : W + koff, b_off[i],
+                         sbase + BM * BK * 2 + i * (NW * 1024));
     };
-    auto issue = [&](int kt, int stage) {               // DMA of this workgroup's k-tile kt into `stage`
-        const int koff = (kt0 + kt) * BK;
-        const uint32_t sbase = lds_base + stage * STAGE_BYTES + wave * 1024;
-#pragma unroll
-        for (int i = 0; i < NGA; ++i) dma_b128(A + koff, a_off[i], sbase + i * (NW * 1024));
-#pragma unroll
-        for (int i = 0; i < NGB; ++i) dma_b128(W + koff, b_off[i], sbase + BM * BK * 2 + i * (NW * 1024));
-    };
+    // DMA of this workgroup's whole k-tile kt into `stage`
+    auto issue = [&](int kt, int stage) { issue_part(kt, stage, 0, NG); };
 
     floatx4_t acc[FM][FN][2][2];
 #pragma unroll
@@ -359,10 +388,28 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
         return *reinterpret_cast<const bf16x8_t *>(tile + lds_off(r, (q * KS + ks) * 4 + q16));
     };
     auto load_b = [&](const uint16_t *tile, int q, bf16x8_t *b) {
+        if constexpr (BKM) {
+            // lane l needs column 16j + l%16 at the k-values 8*(l/16) .. +7 of the k-step.  The
+            // transposing load hands lane i of a 16-lane group element i%4 of the 8-byte chunks
+            // that lanes 4t + i/4 (t = 0..3) point at: lane l points at k-row 8*(l/16) + (l%16)/4
+            // (+4 for the second half) and at columns 16j + 4*(l%4) .. +3.
+            typedef short bkm_shortx4_t __attribute__((ext_vector_type(4)));
+            typedef __attribute__((address_space(3))) bkm_shortx4_t lds_shortx4_t;
+            const int kr = (q * KS + ks) * 32 + 8 * q16 + (c16 >> 2);
 #pragma unroll
-        for (int j = 0; j < FN16; ++j) {
-            const int r = wn * TN + j * 16 + c16;
-            b[j] = *reinterpret_cast<const bf16x8_t *>(tile + BM * BK + lds_off(r, (q * KS + ks) * 4 + q16));
+            for (int j = 0; j < FN16; ++j) {
+                const int chunk = (wn * TN + j * 16) / 8 + ((c16 & 3) >> 1);
+                const uint16_t *src = tile + BM * BK + kr * BN + ((chunk ^ bkm_swz(kr)) << 3) + (c16 & 1) * 4;
+                const bkm_shortx4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_t *)src);
+                const bkm_shortx4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4_t *)(src + 4 * BN));
+                b[j] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < FN16; ++j) {
+                const int r = wn * TN + j * 16 + c16;
+                b[j] = *reinterpret_cast<const bf16x8_t *>(tile + BM * BK + lds_off(r, (q * KS + ks) * 4 + q16));
+            }
         }
     };
 
@@ -575,12 +622,68 @@ static void launch_gemm_bf16_cfg(const void *A, const void *W, int rows, int N, 
     group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
     launch(kern, dim3(grid), dim3(64 * WM * WN * KS), lds, st, (const uint16_t *)A,
                        (const uint16_t *)W, rows, N, K, tiles_m, tiles_n, group_m, ep, nsplit, part,
-                       full_tiles, tail);
+                       full_tiles, tail, 1, (size_t)0, (size_t)0, (size_t)0);
     if (tail > 1) {
         const long total = (long)(ntiles - full_tiles) * BM * (BN / 4);
         launch(gemm_tail_epilogue_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                (const float *)part, tail, full_tiles, tiles_m, tiles_n, group_m, BM, BN, rows, N, total, ep);
     }
+}
+
+// out[b] = A[b] X[b] for nbatch problems with the second operand k-major (X[b]: [K][N], A[b]:
+// [rows][K], `a_bstride` elements apart or shared when 0), bf16 output, no epilogue terms.
+template <int BM, int BN, int WM, int WN, int STAGES>
+static void launch_kmajor_cfg(const void *A, size_t a_bstride, const void *X, int nbatch, int rows,
+                              int N, int K, void *out, hipStream_t st)
+{
+    EpiParams ep{};
+    ep.out0 = out; ep.ld0 = N; ep.split = N; ep.N = N; ep.rows_per_sample = 1;
+    const int tiles_m = (rows + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int ntiles = tiles_m * tiles_n * nbatch;
+    const int grid = (ntiles + 7) / 8 * 8;
+    const size_t lds_stages = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
+    const size_t lds_epi = gemm_epi_lds_bytes(BM, BN, WM, WN, 1);
+    const size_t lds = lds_stages > lds_epi ? lds_stages : lds_epi;
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, STAGES, 1, true>;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    int group_m = (int)lround(sqrt((double)tiles_m * tiles_n * BN / (8.0 * BM)));
+    group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
+    launch(kern, dim3(grid), dim3(64 * WM * WN), lds, st, (const uint16_t *)A, (const uint16_t *)X, rows,
+           N, K, tiles_m, tiles_n, group_m, ep, 1, (float *)nullptr, ntiles, 1, nbatch, a_bstride,
+           (size_t)K * N, (size_t)rows * N);
+}
+
+// Runs out[b] = qt[b] x[b] (qt: [rows][M] per sample or shared, x[b]: [M][d]) on the tiled MFMA
+// kernel when the shape suits it: M a multiple of the 64-wide k-tile, d a multiple of 8, and
+// enough tiles to fill three quarters of the chip.  Returns false (nothing launched) otherwise.
+bool launch_gemm_bf16_kmajor(const void *qt, size_t q_stride, const void *x, int B, int M, int rows,
+                             int d, void *out, hipStream_t st)
+{
+    if (M < BK || M % BK != 0 || d % 8 != 0 || d < 8 || rows < 1 || B < 1) return false;
+    if ((size_t)rows * M * sizeof(uint16_t) >= ((size_t)1 << 32)) return false;   // 32-bit operand offsets
+    struct Cand { int bm, bn; double rate; };
+    const Cand cands[5] = {{256, 256, 1155.0}, {128, 256, 1041.0}, {320, 256, 1300.0},
+                           {192, 256, 1100.0}, {256, 128, 1045.0}};
+    int best = -1;
+    double best_cost = 1e300;
+    for (int i = 0; i < 5; ++i) {
+        const long tiles = (long)((rows + cands[i].bm - 1) / cands[i].bm) *
+                           ((d + cands[i].bn - 1) / cands[i].bn) * B;
+        if (tiles < 192) continue;
+        const double t_tile = 2.0 * cands[i].bm * cands[i].bn * (double)M * 256.0 / (cands[i].rate * 1e6);
+        const double cost = (double)((tiles + 255) / 256) * t_tile;
+        if (cost < best_cost) { best_cost = cost; best = i; }
+    }
+    switch (best) {
+    case 0: launch_kmajor_cfg<256, 256, 2, 4, 2>(qt, q_stride, x, B, rows, d, M, out, st); break;
+    case 1: launch_kmajor_cfg<128, 256, 2, 4, 3>(qt, q_stride, x, B, rows, d, M, out, st); break;
+    case 2: launch_kmajor_cfg<320, 256, 2, 4, 2>(qt, q_stride, x, B, rows, d, M, out, st); break;
+    case 3: launch_kmajor_cfg<192, 256, 2, 4, 2>(qt, q_stride, x, B, rows, d, M, out, st); break;
+    case 4: launch_kmajor_cfg<256, 128, 4, 2, 3>(qt, q_stride, x, B, rows, d, M, out, st); break;
+    default: return false;
+    }
+    return true;
 }
 
 // Sum of the partial tiles of a split contraction + the epilogue (bias, GELU, residual, bf16 or

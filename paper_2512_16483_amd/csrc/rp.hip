@@ -198,6 +198,8 @@ void launch_rp_project(DType dt, const void *qt, size_t q_stride, const void *x,
                        int rows, int d, void *out, hipStream_t st)
 {
     if (dt == DType::BF16) {
+        // large problems on whole k-tiles go to the tiled MFMA kernel of the linear layers
+        if (launch_gemm_bf16_kmajor(qt, q_stride, x, B, M, rows, d, out, st)) return;
         if (rows <= 64 || (rows > 128 && rows <= 192)) {
             dim3 grid((d + kRpBN - 1) / kRpBN, (rows + 63) / 64, B);
             launch(rp_project_bf16_kernel<64>, grid, dim3(256), 0, st, (const uint16_t *)qt, q_stride,

@@ -56,6 +56,49 @@ def test_rp_project_parity(dtype, B, M, rows, d, per_sample):
         assert rel_err(got[b], ref) <= TOL[dtype], (b, rel_err(got[b], ref))
 
 
+@pytest.mark.parametrize("B,M,rows,d,per_sample", [
+    (12, 128, 128, 4096, False),     # 128x256 tiles, two k-tiles on a three-stage ring
+    (12, 64, 64, 4096, True),        # a single k-tile, Q per sample
+    (24, 320, 320, 2048, True),      # 320x256 tiles
+    (16, 256, 250, 3136, False),     # 256x256 tiles, ragged rows and columns
+    (16, 192, 192, 3072, True),      # 192x256 tiles, three k-tiles
+    (32, 512, 500, 384, False),      # 256x128 tiles, ragged rows
+    (3, 1024, 700, 4096, True),      # long contraction, several rounds of workgroups
+])
+def test_rp_project_tiled_path(B, M, rows, d, per_sample):
+    """Shapes on whole 64-token k-tiles with enough output tiles to fill the chip run on the tiled
+    MFMA kernel of the linear layers with the token map as a k-major operand: every tile
+    configuration it can pick, against the oracle on every sample."""
+    x = wl.activations_lowrank(B, M, d, seed=150 + M + rows, bf16=True)
+    Q = _q(B, M, rows, 160 + M + rows, "bf16", per_sample)
+    ctx = _ctx(d, "bf16")
+    out = torch.full((B, rows, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    fv.fvar_rp_project(ctx, _qt_dev(Q, "bf16"), per_sample, to_dev(x, "bf16"), B, M, rows, out)
+    torch.cuda.synchronize()
+    got = to_np(out)
+    assert np.isfinite(got).all()
+    for b in range(B):
+        ref = rp_path.rp_input(Q[b if per_sample else 0], x[b], bf16=True)
+        assert rel_err(got[b], ref) <= TOL["bf16"], (b, rel_err(got[b], ref))
+
+
+def test_rp_project_tiled_path_selection_matrix_bitexact():
+    # products with 1 and 0 are exact: a column-selection Q reproduces the rows bit for bit
+    B, M, rows, d = 12, 128, 128, 4096
+    x = wl.activations_iid(B, M, d, seed=171, bf16=True)
+    rng = np.random.default_rng(6)
+    Q = np.zeros((B, M, rows), np.float32)
+    idx = np.stack([rng.permutation(M)[:rows] for _ in range(B)])
+    for b in range(B):
+        Q[b, idx[b], np.arange(rows)] = 1.0
+    ctx = _ctx(d, "bf16")
+    out = torch.empty((B, rows, d), dtype=torch.bfloat16, device="cuda")
+    fv.fvar_rp_project(ctx, _qt_dev(Q, "bf16"), True, to_dev(x, "bf16"), B, M, rows, out)
+    torch.cuda.synchronize()
+    for b in range(B):
+        assert np.array_equal(to_np(out[b]), x[b][idx[b]])
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_rp_project_with_selection_matrix_is_the_gather(dtype):
     # products with 1 and 0 are exact, so a column-selection Q must reproduce the rows bit for bit
