@@ -6,8 +6,9 @@
 // (fp32 accumulation; on operands with realistic bit activity the chip sustains a higher clock
 // on this shape than on 32x32x16: half the accumulator register traffic per flop).  Tiles are
 // DMA-ed global -> LDS (no register staging) into a ring of stages ahead of the MFMAs; operand
-// fragments are read from LDS a few MFMA groups ahead of their use.  LDS rows are 128 B; the 16-byte chunk index is XOR-swizzled with (row/2)%8 so
-// that the ds_read_b128 operand fetches of 16 consecutive rows cover all 64 banks exactly once.
+// fragments are read from LDS a few MFMA groups ahead of their use.  LDS rows are 128 B; the
+// 16-byte chunk index is XOR-swizzled with (row/2)%8 so that the ds_read_b128 operand fetches of
+// 16 consecutive rows cover all 64 banks exactly once.
 // Workgroup ids are remapped so that each XCD (own L2) works on a compact patch of the tile
 // grid.  Bigger tiles cut the L1/LDS traffic per flop (a 128x128 tile needs the full 64 B/clk of
 // the CU's vector L1 at peak MFMA rate, a 256x256 tile half of it) but quantise badly on the few
@@ -75,8 +76,9 @@ __device__ __forceinline__ int bkm_swz(int row)
 
 // Epilogue of the bf16 kernel.  The accumulators of a wavefront are kept per 32x32 region
 // [i][j] as 2x2 blocks [bi][bj] of the 16x16 MFMA: entry e of a block holds row
-// 16*bi + 4*(lane/16) + e, column 16*bj + lane%16 of the region.  Each wavefront applies bias and GELU, packs to
-// bf16 (adjacent lanes swap one value per row pair so that a lane owns two neighbouring columns)
+// 16*bi + 4*(lane/16) + e, column 16*bj + lane%16 of the region.  Each wavefront applies bias
+// and GELU, packs to bf16 (adjacent lanes swap one value per row pair so that a lane owns two
+// neighbouring columns)
 // and parks its sub-tile row-major in a private LDS region; it then reads the sub-tile back as
 // 16-byte row chunks, adds the residual (16-byte loads) and stores 16 bytes per lane, so a store
 // instruction covers whole 128-byte row segments.  The destination row pointers (plain output,
@@ -499,7 +501,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
                 for (int e = 0; e < 16; ++e) acc[i][j][(e >> 3) & 1][(e >> 2) & 1][e & 3] += red[((i * FN + j) * 16 + e) * 64];
     }
     if (ranges > 1) {
-        // partial tile, fp32: the 32 lanes of a half-wavefront cover 128 contiguous bytes of a row.
+        // partial tile, fp32: 16 neighbouring lanes cover 64 contiguous bytes of a row.
         // Divided problem: [range][rows][N]; divided tail: [tail tile][range][BM][BN].
         const bool tail = tail_split > 1;
         float *dst = tail ? part + ((size_t)(tile_id - full_tiles) * tail_split + split) * (BM * BN)
