@@ -118,6 +118,29 @@ def test_infinity2b_batch32_keep_and_rank_sweep():
             assert torch.equal(blk.K, K_dense)
 
 
+@pytest.mark.parametrize("side", [48, 64])
+def test_infinity2b_batch32_late_scales(side):
+    """Infinity-2B shape at batch 32 on the 48x48 and 64x64 scales (22 144 / 39 328 rows through
+    the linear layers, 4813 / 7654 keys): the benchmark's launch shape, one sample against the
+    oracle, every sample through the properties that hold at any size."""
+    W = wl.WORKLOADS["infinity2b_1024_b32_bf16"]
+    B, d, H, F, r = W.batch, W.hidden, W.heads, W.ffn_hidden, W.rank
+    M, Lp, k = W.tokens(side), W.prev_len(side), W.keep(side)
+    x, w, Kp, Vp = draw_inputs(W, side, B, 1400 + side)
+    Wc, Gc = wl.direct_factors(B, M, r, d, seed=4400 + side, bf16=True)
+    blk = GpuBlock(d, H, F, "bf16", w, Kp, Vp, Lp + M)
+    xd = to_dev(x, "bf16")
+    s, keep, drop = blk.score_select(xd, k)
+    y_keep = blk.pruned(xd, keep, k)
+    y = blk.fill(y_keep, keep, drop, M, to_dev(Wc, "bf16"), to_dev(Gc, "bf16"))
+    torch.cuda.synchronize()
+    keep_h, drop_h, y_h, yk_h = keep.cpu().numpy(), drop.cpu().numpy(), to_np(y), to_np(y_keep)
+    assert np.isfinite(y_h).all()
+    check_other_samples(range(B), s, keep_h, drop_h, y_h, yk_h, x, k, Wc, Gc, np.random.default_rng(side))
+    compare_sample(f"infinity2b b32 s{side}", 17, blk, Lp, k, x, w, H, Kp, Vp, Wc, Gc, keep_h, drop_h,
+                   yk_h, y_h)
+
+
 def test_large_shape_scale80_batch4():
     """Hidden 4096, 32 heads of 128, rank 128, batch 4 at the 80x80 scale: 1600 kept rows of 6400
     against 10521 cached rows (12121 keys).  One sample against the oracle."""
