@@ -1,10 +1,10 @@
 """GPU parity at the geometry each bf16 workload is named for: the late scales 48 and 64 of the
 Infinity-2B-shaped model at batch 1 (long caches: the key axis of the attention and the
 contraction axis of the O / FC2 layers are divided between workgroups), the same model at
-batch 32 with the keep-ratio and rank sweep, and the 80x80 scale of the 4096-hidden shape at
-batch 4.  The GPU runs the benchmark's launch configuration (full batch); the oracle computes
-one or two samples element by element, the other samples are checked through properties that
-hold at any size.  Bars as everywhere: indices bit-exact, bf16 outputs within 2e-2."""
+batch 32 with the keep-ratio and rank sweep and on its larger scales, the 80x80 scale of the
+4096-hidden shape at batch 4, and the STAR-shaped stand-in at its late scale.  The GPU runs the
+benchmark's launch configuration (full batch); the oracle computes one or two samples element by
+element, the other samples are checked through properties that hold at any size.  Bars as everywhere: indices bit-exact, bf16 outputs within 2e-2."""
 import numpy as np
 import pytest
 import torch
@@ -139,6 +139,27 @@ def test_infinity2b_batch32_late_scales(side):
     check_other_samples(range(B), s, keep_h, drop_h, y_h, yk_h, x, k, Wc, Gc, np.random.default_rng(side))
     compare_sample(f"infinity2b b32 s{side}", 17, blk, Lp, k, x, w, H, Kp, Vp, Wc, Gc, keep_h, drop_h,
                    yk_h, y_h)
+
+
+def test_star_shaped_scale64_batch4():
+    """The STAR-shaped stand-in (hidden 2048, keep 22/125, rank 64) at its late scale, batch 4:
+    721 kept rows of 4096 against 6425 cached rows, one sample against the oracle."""
+    W = wl.WORKLOADS["star_shaped_1024_bf16"]
+    side = 64
+    B, d, H, F, r = W.batch, W.hidden, W.heads, W.ffn_hidden, W.rank
+    M, Lp, k = W.tokens(side), W.prev_len(side), W.keep(side)
+    assert (M, k) == (4096, 721)
+    x, w, Kp, Vp = draw_inputs(W, side, B, 1500)
+    Wc, Gc = wl.direct_factors(B, M, r, d, seed=4500, bf16=True)
+    blk = GpuBlock(d, H, F, "bf16", w, Kp, Vp, W.total_len(), scales=W.scales)
+    xd = to_dev(x, "bf16")
+    s, keep, drop = blk.score_select(xd, k)
+    y_keep = blk.pruned(xd, keep, k)
+    y = blk.fill(y_keep, keep, drop, M, to_dev(Wc, "bf16"), to_dev(Gc, "bf16"))
+    torch.cuda.synchronize()
+    keep_h, drop_h, y_h, yk_h = keep.cpu().numpy(), drop.cpu().numpy(), to_np(y), to_np(y_keep)
+    check_other_samples(range(B), s, keep_h, drop_h, y_h, yk_h, x, k, Wc, Gc, np.random.default_rng(64))
+    compare_sample("star-shaped s64", 1, blk, Lp, k, x, w, H, Kp, Vp, Wc, Gc, keep_h, drop_h, yk_h, y_h)
 
 
 def test_large_shape_scale80_batch4():
