@@ -166,6 +166,8 @@ void launch_cache_fill(DType dt, const void *y_keep, const int32_t *idx_keep, co
 
 // out[b] = qt[b] x[b]:  qt:[rows,M] (sample stride q_stride elements, 0 = shared), x:[B,M,d],
 // out:[B,rows,d].  M must be a multiple of the 16-byte chunk (8 bf16 / 4 fp32 elements).
+bool launch_gemm_bf16_batched_f32(const void *A, const void *W, int nbatch, int rows, int N, int K,
+                                  float *out, hipStream_t st);
 bool launch_gemm_bf16_kmajor(const void *qt, size_t q_stride, const void *x, int B, int M, int rows,
                              int d, void *out, hipStream_t st);
 void launch_rp_project(DType dt, const void *qt, size_t q_stride, const void *x, int B, int M,

@@ -342,6 +342,10 @@ void launch_factor_t(DType dt, const void *cache, const void *g_c, int B, int M,
                      hipStream_t st)
 {
     if (dt == DType::BF16) {
+        // many samples at once (the caches of all blocks of a scale): T = C G^T is an ordinary
+        // linear layer per sample, run on the tiled MFMA kernel with fp32 output
+        if (factor_t_parts(dt, B, M) == 1 && launch_gemm_bf16_batched_f32(cache, g_c, B, M, r, d, T, st))
+            return;
         dim3 grid((M + 63) / 64, factor_t_parts(dt, B, M), B);
         const int rt = (r + 31) / 32;
         const size_t lds = (size_t)4 * 64 * 32 * rt * sizeof(float);

@@ -244,6 +244,7 @@ constexpr size_t gemm_epi_lds_bytes(int BM, int BN, int WM, int WN, int KS)
 // the B fragments come from the transposing LDS load.  This mode runs `nbatch` independent
 // problems of one shape in one launch (operands and output `*_bstride` elements apart), whole
 // tiles only (no division of the contraction), K a multiple of 64 and N a multiple of 8.
+// nbatch > 1 is also available with the ordinary operand layout (whole tiles only).
 template <int BM, int BN, int WM, int WN, int STAGES, int KS, bool BKM = false>
 __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     const uint16_t *__restrict__ A_in, const uint16_t *__restrict__ W_in, int rows, int N, int K,
@@ -271,7 +272,7 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
     //    workgroups whose partial tiles go to `part` tile by tile; every XCD gets an eighth of
     //    the whole tiles first and an eighth of the divided ones after them.
     // Partial tiles are summed and finished by a second kernel.
-    const int ntiles = tiles_m * tiles_n * (BKM ? nbatch : 1);
+    const int ntiles = tiles_m * tiles_n * nbatch;
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
     int pid, split = 0, ranges = 1;
     if (tail_split > 1) {
@@ -295,12 +296,12 @@ __global__ __launch_bounds__(64 * WM * WN * KS) void gemm_bf16_kernel(
         ranges = nsplit;
     }
     const int tile_id = pid;
-    if (BKM) {
+    if (BKM || nbatch > 1) {
         const int per = tiles_m * tiles_n, bidx = pid / per;
         pid -= bidx * per;
         A += (size_t)bidx * a_bstride;
         W += (size_t)bidx * w_bstride;
-        ep.out0 = reinterpret_cast<uint16_t *>(ep.out0) + (size_t)bidx * o_bstride;
+        ep.out0 = reinterpret_cast<char *>(ep.out0) + (size_t)bidx * o_bstride * (ep.out_f32 ? 4 : 2);
     }
     // consecutive tile ids run down group_m row tiles, then across the columns: the contiguous
     // id range of one XCD is a patch of about group_m x (tiles/8/group_m) tiles
@@ -654,6 +655,45 @@ static void launch_kmajor_cfg(const void *A, size_t a_bstride, const void *X, in
     launch(kern, dim3(grid), dim3(64 * WM * WN), lds, st, (const uint16_t *)A, (const uint16_t *)X, rows,
            N, K, tiles_m, tiles_n, group_m, ep, 1, (float *)nullptr, ntiles, 1, nbatch, a_bstride,
            (size_t)K * N, (size_t)rows * N);
+}
+
+// out[b] = A[b] W[b]^T in fp32 for nbatch problems of one shape (A[b]: [rows][K], W[b]: [N][K], both
+// bf16 and `rows*K` / `N*K` elements apart; out[b]: [rows][N]) on the tiled MFMA kernel, when the
+// shape suits it: K a multiple of the 64-wide k-tile, N <= 256 and enough tiles to fill three
+// quarters of the chip.  Returns false (nothing launched) otherwise.
+template <int BM, int BN, int WM, int WN, int STAGES>
+static void launch_batched_f32_cfg(const void *A, const void *W, int nbatch, int rows, int N, int K,
+                                   float *out, hipStream_t st)
+{
+    EpiParams ep{};
+    ep.out0 = out; ep.ld0 = N; ep.split = N; ep.N = N; ep.rows_per_sample = 1; ep.out_f32 = 1;
+    const int tiles_m = (rows + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int ntiles = tiles_m * tiles_n * nbatch;
+    const int grid = (ntiles + 7) / 8 * 8;
+    const size_t lds_stages = (size_t)STAGES * (BM + BN) * BK * sizeof(uint16_t);
+    const size_t lds_epi = gemm_epi_lds_bytes(BM, BN, WM, WN, 1);
+    const size_t lds = lds_stages > lds_epi ? lds_stages : lds_epi;
+    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, STAGES, 1, false>;
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    int group_m = (int)lround(sqrt((double)tiles_m * tiles_n * BN / (8.0 * BM)));
+    group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
+    launch(kern, dim3(grid), dim3(64 * WM * WN), lds, st, (const uint16_t *)A, (const uint16_t *)W, rows,
+           N, K, tiles_m, tiles_n, group_m, ep, 1, (float *)nullptr, ntiles, 1, nbatch,
+           (size_t)rows * K, (size_t)N * K, (size_t)rows * N);
+}
+
+bool launch_gemm_bf16_batched_f32(const void *A, const void *W, int nbatch, int rows, int N, int K,
+                                  float *out, hipStream_t st)
+{
+    if (K < BK || K % BK != 0 || N < 1 || N > 256 || rows < 1 || nbatch < 1) return false;
+    if ((size_t)rows * K * sizeof(uint16_t) >= ((size_t)1 << 32)) return false;   // 32-bit operand offsets
+    const bool narrow = N <= 128;
+    const long tiles = (long)((rows + 255) / 256) * nbatch;
+    if (tiles < 192) return false;
+    if (narrow) launch_batched_f32_cfg<256, 128, 4, 2, 3>(A, W, nbatch, rows, N, K, out, st);
+    else launch_batched_f32_cfg<256, 256, 2, 4, 2>(A, W, nbatch, rows, N, K, out, st);
+    return true;
 }
 
 // Runs out[b] = qt[b] x[b] (qt: [rows][M] per sample or shared, x[b]: [M][d]) on the tiled MFMA

@@ -405,3 +405,23 @@ def test_cache_factors_depth30_launch_shape():
         Wo, Go = factors.stored_factors(Cm[b], Q[0], bf16=True)
         assert rel_err(to_np(g_c[b]), Go) <= TOL["bf16"]
         assert rel_err(to_np(w_c[b]), Wo) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("B,M,d,r", [(200, 256, 512, 64), (192, 304, 448, 72), (96, 512, 1024, 128)])
+def test_cache_factors_many_samples(B, M, d, r):
+    """The caches of all blocks of a scale in one call (hundreds of samples): the projection
+    G_c = Q^T C and the product T = C G_c^T then run on the tiled MFMA kernel of the linear
+    layers (k-major operand / batched fp32 output).  Three samples against the oracle."""
+    Cm = wl.round_to_bf16(wl.cached_feature(B, M, d, max(8, r // 2), seed=4300 + r, noise=0.1))
+    Q = _q(B, M, r, 4301 + r, "bf16", False)
+    ctx = _ctx(d, "bf16")
+    w_c = torch.full((B, M, r), float("nan"), dtype=torch.bfloat16, device="cuda")
+    g_c = torch.full((B, r, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(fv.fvar_factors_workspace_bytes(ctx, B, M, r), dtype=torch.uint8, device="cuda")
+    fv.fvar_cache_factors(ctx, to_dev(Cm, "bf16"), _qt_dev(Q, "bf16"), False, B, M, r, 0.0, w_c, g_c, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(w_c.float()).all() and torch.isfinite(g_c.float()).all()
+    for b in (0, B // 3, B - 1):
+        Wo, Go = factors.stored_factors(Cm[b], Q[0], bf16=True)
+        assert rel_err(to_np(g_c[b]), Go) <= TOL["bf16"], (b, rel_err(to_np(g_c[b]), Go))
+        assert rel_err(to_np(w_c[b]), Wo) <= TOL["bf16"], (b, rel_err(to_np(w_c[b]), Wo))
