@@ -281,11 +281,11 @@ __global__ __launch_bounds__(256) void spd_inverse_kernel(const double *__restri
 }
 
 // ------------------------------------------------------------------ W = T S^{-1}
-// Workgroup = 64 rows of T; S^{-1} is staged in LDS (fp64).  Wavefront w produces the w-th
-// quarter of the r columns, lane = row: every lane of a wavefront reads the same S^{-1} entries
-// (LDS broadcast) and walks its own row of T (the sum of its one or two slices).
-// CQ = columns per wavefront (r / 4 rounded up).
-template <typename TT, int CQ>
+// Workgroup = 64 * RPL rows of T; S^{-1} is staged in LDS (fp64).  Wavefront w produces the w-th
+// quarter of the r columns, a lane owns RPL rows (64 apart): every lane of a wavefront reads the
+// same S^{-1} entries (LDS broadcast, one read serves RPL FMAs) and walks its own rows of T (the
+// sum of their one or two slices).  CQ = columns per wavefront (r / 4 rounded up).
+template <typename TT, int CQ, int RPL>
 __global__ __launch_bounds__(256) void w_kernel(const float *__restrict__ T, int t_parts,
                                                 size_t t_part_stride,
                                                 const double *__restrict__ Sinv, int M, int r,
@@ -300,30 +300,45 @@ __global__ __launch_bounds__(256) void w_kernel(const float *__restrict__ T, int
         Si[idx] = c < r ? Sg[(size_t)t * r + c] : 0.0;
     }
     __syncthreads();
-    const int row = blockIdx.x * 64 + lane;
-    const float *trow = T + ((size_t)b * M + min(row, M - 1)) * r;
-    double acc[CQ];
+    const int row0 = blockIdx.x * (64 * RPL) + lane;
+    const float *trow[RPL];
 #pragma unroll
-    for (int q = 0; q < CQ; ++q) acc[q] = 0.0;
+    for (int p = 0; p < RPL; ++p) trow[p] = T + ((size_t)b * M + min(row0 + 64 * p, M - 1)) * r;
+    double acc[RPL][CQ];
+#pragma unroll
+    for (int p = 0; p < RPL; ++p)
+#pragma unroll
+        for (int q = 0; q < CQ; ++q) acc[p][q] = 0.0;
     const double *sw = Si + wave * CQ;
     for (int t0 = 0; t0 < r; t0 += 4) {            // r is a multiple of 4
-        float4 tv = *reinterpret_cast<const float4 *>(trow + t0);
-        if (t_parts > 1) {                         // second slice of the contraction axis
-            const float4 tp = *reinterpret_cast<const float4 *>(trow + t_part_stride + t0);
-            tv.x += tp.x; tv.y += tp.y; tv.z += tp.z; tv.w += tp.w;
+        double td[RPL][4];
+#pragma unroll
+        for (int p = 0; p < RPL; ++p) {
+            float4 tv = *reinterpret_cast<const float4 *>(trow[p] + t0);
+            if (t_parts > 1) {                     // second slice of the contraction axis
+                const float4 tp = *reinterpret_cast<const float4 *>(trow[p] + t_part_stride + t0);
+                tv.x += tp.x; tv.y += tp.y; tv.z += tp.z; tv.w += tp.w;
+            }
+            td[p][0] = (double)tv.x; td[p][1] = (double)tv.y; td[p][2] = (double)tv.z; td[p][3] = (double)tv.w;
         }
-        const double td[4] = {(double)tv.x, (double)tv.y, (double)tv.z, (double)tv.w};
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int q = 0; q < CQ; ++q) acc[q] = fma(td[u], sw[(t0 + u) * PW + q], acc[q]);
+            for (int q = 0; q < CQ; ++q) {
+                const double sv = sw[(t0 + u) * PW + q];
+#pragma unroll
+                for (int p = 0; p < RPL; ++p) acc[p][q] = fma(td[p][u], sv, acc[p][q]);
+            }
     }
-    if (row < M) {
+#pragma unroll
+    for (int p = 0; p < RPL; ++p) {
+        const int row = row0 + 64 * p;
+        if (row >= M) continue;
         TT *out = w_c + ((size_t)b * M + row) * r;
 #pragma unroll
         for (int q = 0; q < CQ; ++q) {
             const int c = wave * CQ + q;
-            if (c < r) Elem<TT>::store(out + c, (float)acc[q]);
+            if (c < r) Elem<TT>::store(out + c, (float)acc[p][q]);
         }
     }
 }
@@ -398,16 +413,20 @@ static void launch_w_t(const float *T, int t_parts, const double *Sinv, int B, i
                        hipStream_t st)
 {
     const size_t t_stride = (size_t)B * M * r;
-    dim3 grid((M + 63) / 64, B);
+    // two rows per lane once that still leaves a workgroup for every CU
+    const bool two = (long)B * ((M + 127) / 128) >= 256;
+    dim3 grid(two ? (M + 127) / 128 : (M + 63) / 64, B);
     const int cq = (r + 3) / 4;
 #define FVAR_W(CQ)                                                                                 \
     do {                                                                                           \
         const size_t lds = (size_t)r * 4 * CQ * sizeof(double);                                    \
+        auto k1 = w_kernel<TT, CQ, 1>;                                                             \
+        auto k2 = w_kernel<TT, CQ, 2>;                                                             \
+        auto kern = two ? k2 : k1;                                                                 \
         if (lds > 48 * 1024)                                                                       \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(w_kernel<TT, CQ>),            \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),                        \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);       \
-        launch((w_kernel<TT, CQ>), grid, dim3(256), lds, st, T, t_parts, t_stride, Sinv, M, r,         \
-               (TT *)w_c);            \
+        launch(kern, grid, dim3(256), lds, st, T, t_parts, t_stride, Sinv, M, r, (TT *)w_c);       \
     } while (0)
     if (cq <= 8) FVAR_W(8);
     else if (cq <= 16) FVAR_W(16);
