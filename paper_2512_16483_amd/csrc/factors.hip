@@ -311,24 +311,28 @@ __global__ __launch_bounds__(256) void w_kernel(const float *__restrict__ T, int
         for (int q = 0; q < CQ; ++q) acc[p][q] = 0.0;
     const double *sw = Si + wave * CQ;
     for (int t0 = 0; t0 < r; t0 += 4) {            // r is a multiple of 4
-        double td[RPL][4];
+        float4 tv[RPL];
 #pragma unroll
         for (int p = 0; p < RPL; ++p) {
-            float4 tv = *reinterpret_cast<const float4 *>(trow[p] + t0);
+            tv[p] = *reinterpret_cast<const float4 *>(trow[p] + t0);
             if (t_parts > 1) {                     // second slice of the contraction axis
                 const float4 tp = *reinterpret_cast<const float4 *>(trow[p] + t_part_stride + t0);
-                tv.x += tp.x; tv.y += tp.y; tv.z += tp.z; tv.w += tp.w;
+                tv[p].x += tp.x; tv[p].y += tp.y; tv[p].z += tp.z; tv[p].w += tp.w;
             }
-            td[p][0] = (double)tv.x; td[p][1] = (double)tv.y; td[p][2] = (double)tv.z; td[p][3] = (double)tv.w;
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 4; ++u) {
+            double td[RPL];
+#pragma unroll
+            for (int p = 0; p < RPL; ++p)
+                td[p] = (double)(u == 0 ? tv[p].x : u == 1 ? tv[p].y : u == 2 ? tv[p].z : tv[p].w);
 #pragma unroll
             for (int q = 0; q < CQ; ++q) {
                 const double sv = sw[(t0 + u) * PW + q];
 #pragma unroll
-                for (int p = 0; p < RPL; ++p) acc[p][q] = fma(td[p][u], sv, acc[p][q]);
+                for (int p = 0; p < RPL; ++p) acc[p][q] = fma(td[p], sv, acc[p][q]);
             }
+        }
     }
 #pragma unroll
     for (int p = 0; p < RPL; ++p) {

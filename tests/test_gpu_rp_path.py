@@ -59,7 +59,7 @@ def test_rp_project_parity(dtype, B, M, rows, d, per_sample):
 @pytest.mark.parametrize("B,M,rows,d,per_sample", [
     (12, 128, 128, 4096, False),     # 128x256 tiles, two k-tiles on a three-stage ring
     (12, 64, 64, 4096, True),        # a single k-tile, Q per sample
-    (24, 320, 320, 2048, True),      # 320x256 tiles
+    (24, 320, 320, 2048, True),      # rows of one and a quarter 256-row tiles
     (16, 256, 250, 3136, False),     # 256x256 tiles, ragged rows and columns
     (16, 192, 192, 3072, True),      # 192x256 tiles, three k-tiles
     (32, 512, 500, 384, False),      # 256x128 tiles, ragged rows
