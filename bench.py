@@ -28,9 +28,9 @@ WORKLOAD = "large_1280_bf16"
 # under profiles/ is named in the entry).  An entry is dropped (traffic: null) whenever gemm.hip
 # changes, until the counters are taken again.
 GEMM_TRAFFIC = {
-    "large_1280_bf16": {"bytes_per_launch": 1.329e9,
+    "large_1280_bf16": {"bytes_per_launch": 1.333e9,
                         "source": "profiles/pruned_chain_large_1280_bf16_hbm_counters.txt"},
-    "infinity2b_1024_b32_bf16": {"bytes_per_launch": 1.777e9,
+    "infinity2b_1024_b32_bf16": {"bytes_per_launch": 1.769e9,
                                  "source": "profiles/pruned_chain_infinity2b_1024_b32_bf16_hbm_counters.txt"},
 }
 SWEEP_WORKLOAD = "infinity2b_1024_b32_bf16"
